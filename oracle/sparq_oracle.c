@@ -1,0 +1,229 @@
+/*
+ * SPARQ CPU oracle -- TEST INFRASTRUCTURE ONLY (see sparq_oracle.h).
+ *
+ * Written for clarity, one paper step per function, no blocking, no fusion.
+ * The only concession to run time is an OpenMP "parallel for" over
+ * independent rows.
+ */
+#include "sparq_oracle.h"
+
+#include <stdlib.h>
+#include <string.h>
+
+/* ------------------------------------------------------------------------ */
+/* bSPARQ (Section 3.1)                                                      */
+/* ------------------------------------------------------------------------ */
+
+/* Position of the most significant toggled bit of x > 0 (Section 3.1: the
+ * window is found by searching for the first most significant toggled bit). */
+static int leading_one(int x)
+{
+    int p = -1;
+    while (x > 0) {
+        x >>= 1;
+        ++p;
+    }
+    return p;
+}
+
+int sparq_ref_trim_value(int x, int n, uint32_t S, int round_nearest, int *shift_out)
+{
+    int s = 0;
+    if (x > 0) {
+        const int p = leading_one(x);
+        /* Smallest allowed placement whose top bit s+n-1 reaches the leading
+         * one.  With every placement allowed this is s = p-n+1, the paper's
+         * example 27 -> bits [4:1]; with 3opt the same value gets [5:2] and
+         * with 2opt [7:4] (Section 3.1). */
+        while (s <= 8 && !(((S >> s) & 1u) && s + n - 1 >= p))
+            ++s;
+    }
+    int q = x >> s;                          /* plain trim: drop the s residual LSBs */
+    if (round_nearest && s > 0) {
+        q = (x + (1 << (s - 1))) >> s;       /* round half up on the residual LSBs   */
+        if (q > (1 << n) - 1)
+            q = (1 << n) - 1;                /* carry out of the window saturates    */
+    }
+    if (shift_out)
+        *shift_out = s;
+    return q << s;
+}
+
+/* ------------------------------------------------------------------------ */
+/* mode handling                                                             */
+/* ------------------------------------------------------------------------ */
+
+uint32_t sparq_ref_wide_shift_mask(int32_t n, uint32_t shift_mask)
+{
+    /* A 2n-bit window at shift t is served by the two n-bit multipliers of
+     * Eq. 4 as halves at shifts t+n and t, so both must be placement options. */
+    uint32_t wide = 0;
+    for (int t = 0; t + 2 * n <= 8; ++t)
+        if (((shift_mask >> t) & 1u) && ((shift_mask >> (t + n)) & 1u))
+            wide |= 1u << t;
+    return wide;
+}
+
+int sparq_ref_mode_check(const sparq_ref_mode *mode)
+{
+    if (!mode)
+        return 1;
+    const int n = mode->window_bits;
+    if (n == 8)
+        return 0;                            /* plain 8-bit layer, nothing else matters */
+    if (n != 2 && n != 3 && n != 4)
+        return 1;
+    const uint32_t S = mode->shift_mask;
+    if (S >> (8 - n + 1))
+        return 1;                            /* a window may not stick out above bit 7  */
+    if (!(S & 1u) || !((S >> (8 - n)) & 1u))
+        return 1;                            /* small values and bit 7 must be coverable */
+    if (mode->round_nearest != 0 && mode->round_nearest != 1)
+        return 1;
+    if (mode->pair != 0 && mode->pair != 1)
+        return 1;
+    if (mode->pair) {
+        const uint32_t S2 = sparq_ref_wide_shift_mask(n, S);
+        if (!(S2 & 1u) || !((S2 >> (8 - 2 * n)) & 1u))
+            return 1;
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/* vSPARQ over one channel vector (Section 3.2, Eq. 2)                       */
+/* ------------------------------------------------------------------------ */
+
+static void trim_vector(const uint8_t *x, uint8_t *y, int32_t C, const sparq_ref_mode *mode)
+{
+    const int n = mode->window_bits;
+    if (n == 8) {
+        memmove(y, x, (size_t)C);
+        return;
+    }
+    const uint32_t S = mode->shift_mask;
+    const int R = mode->round_nearest;
+    if (!mode->pair) {
+        for (int32_t c = 0; c < C; ++c)
+            y[c] = (uint8_t)sparq_ref_trim_value(x[c], n, S, R, NULL);
+        return;
+    }
+    const uint32_t S2 = sparq_ref_wide_shift_mask(n, S);
+    for (int32_t c = 0; c < C; c += 2) {
+        const int a = x[c];
+        const int b = (c + 1 < C) ? x[c + 1] : 0;    /* odd tail: implicit zero partner */
+        int ta, tb;
+        if (a == 0 || b == 0) {
+            /* One of the two is zero: the other spans both budgets, 2n bits
+             * (n = 4: all eight bits, the value is untouched). */
+            ta = sparq_ref_trim_value(a, 2 * n, S2, R, NULL);
+            tb = sparq_ref_trim_value(b, 2 * n, S2, R, NULL);
+        } else {
+            ta = sparq_ref_trim_value(a, n, S, R, NULL);
+            tb = sparq_ref_trim_value(b, n, S, R, NULL);
+        }
+        y[c] = (uint8_t)ta;
+        if (c + 1 < C)
+            y[c + 1] = (uint8_t)tb;
+    }
+}
+
+int sparq_trim_ref(const uint8_t *x, uint8_t *y, int64_t rows, int32_t C,
+                   const sparq_ref_mode *mode)
+{
+    if (!x || !y || rows < 0 || C <= 0 || sparq_ref_mode_check(mode))
+        return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        trim_vector(x + r * C, y + r * C, C, mode);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/* trimmed convolution (Eq. 1 with the vector ordered kh, kw, c)             */
+/* ------------------------------------------------------------------------ */
+
+int sparq_conv_gemm_ref(const uint8_t *x, const int8_t *w,
+                        const sparq_ref_conv *d, const sparq_ref_mode *mode,
+                        const int64_t *row_idx, int64_t n_rows,
+                        int32_t *acc, const float *scale, double *out)
+{
+    if (!x || !w || !d || sparq_ref_mode_check(mode))
+        return 1;
+    if (d->B <= 0 || d->H <= 0 || d->W <= 0 || d->C <= 0 || d->N <= 0 ||
+        d->KH <= 0 || d->KW <= 0 || d->stride_h <= 0 || d->stride_w <= 0 ||
+        d->pad_h < 0 || d->pad_w < 0)
+        return 1;
+    if (d->H + 2 * d->pad_h < d->KH || d->W + 2 * d->pad_w < d->KW)
+        return 1;
+    if (out && !scale)
+        return 1;
+    const int64_t Ho = (d->H + 2 * d->pad_h - d->KH) / d->stride_h + 1;
+    const int64_t Wo = (d->W + 2 * d->pad_w - d->KW) / d->stride_w + 1;
+    const int64_t M = (int64_t)d->B * Ho * Wo;
+    const int64_t rows = row_idx ? n_rows : M;
+    if (row_idx)
+        for (int64_t i = 0; i < rows; ++i)
+            if (row_idx[i] < 0 || row_idx[i] >= M)
+                return 1;
+
+    /* Step 1: trim the input tensor, pixel by pixel along the channels. */
+    const int64_t pixels = (int64_t)d->B * d->H * d->W;
+    uint8_t *xt = (uint8_t *)malloc((size_t)(pixels * d->C));
+    if (!xt)
+        return 1;
+    sparq_trim_ref(x, xt, pixels, d->C, mode);
+
+    /* Step 2: every output is the integer dot product over its receptive
+     * field; positions outside the image contribute zero. */
+    int overflow = 0;
+#pragma omp parallel for schedule(static) reduction(| : overflow)
+    for (int64_t i = 0; i < rows; ++i) {
+        const int64_t m = row_idx ? row_idx[i] : i;
+        const int64_t ox = m % Wo;
+        const int64_t oy = (m / Wo) % Ho;
+        const int64_t b = m / (Wo * Ho);
+        for (int32_t n = 0; n < d->N; ++n) {
+            int64_t sum = 0;
+            for (int32_t kh = 0; kh < d->KH; ++kh) {
+                const int64_t iy = oy * d->stride_h - d->pad_h + kh;
+                if (iy < 0 || iy >= d->H)
+                    continue;
+                for (int32_t kw = 0; kw < d->KW; ++kw) {
+                    const int64_t ix = ox * d->stride_w - d->pad_w + kw;
+                    if (ix < 0 || ix >= d->W)
+                        continue;
+                    const uint8_t *xp = xt + ((b * d->H + iy) * d->W + ix) * d->C;
+                    const int8_t *wp = w + (((int64_t)n * d->KH + kh) * d->KW + kw) * d->C;
+                    for (int32_t c = 0; c < d->C; ++c)
+                        sum += (int64_t)xp[c] * (int64_t)wp[c];
+                }
+            }
+            if (sum > INT32_MAX || sum < INT32_MIN)
+                overflow = 1;
+            if (acc)
+                acc[i * d->N + n] = (int32_t)sum;
+            if (out)
+                out[i * d->N + n] = (double)sum * (double)scale[n];
+        }
+    }
+    free(xt);
+    return overflow ? 2 : 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/* dequantisation (Section 5: per-layer activation scale times per-kernel    */
+/* weight scale, folded into one factor per output channel)                  */
+/* ------------------------------------------------------------------------ */
+
+int sparq_dequant_ref(const int32_t *acc, const float *scale, double *out,
+                      int64_t M, int32_t N)
+{
+    if (!acc || !scale || !out || M < 0 || N <= 0)
+        return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int32_t n = 0; n < N; ++n)
+            out[m * N + n] = (double)acc[m * N + n] * (double)scale[n];
+    return 0;
+}

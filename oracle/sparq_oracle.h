@@ -1,0 +1,89 @@
+/*
+ * SPARQ CPU oracle -- TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, step-by-step host implementation of the SPARQ activation
+ * trim (bSPARQ, Section 3.1; vSPARQ, Section 3.2, Eq. 1-2) followed by the
+ * integer dot product of Eq. 1 arranged as a convolution, and the
+ * per-output-channel dequantisation implied by the quantisation scheme of
+ * Section 5.  It exists to check the GPU library and to serve as the timed
+ * CPU baseline.  Nothing in the product path may call it, and it shares no
+ * code, header, table or helper with the GPU library.
+ *
+ * All pointers are HOST pointers.  Every function returns 0 on success and a
+ * positive code on a rejected argument (1 = invalid argument).
+ *
+ * Readings of points the paper leaves open:
+ *   - rounding "according to the residual LSBs" (Section 3.1) is round half
+ *     up inside the chosen window;
+ *   - the window position is fixed by the leading one of the UNROUNDED value
+ *     and a rounding carry out of the window saturates at 2^n - 1;
+ *   - the dot-product vector of Eq. 1 is ordered (kh, kw, c) with the input
+ *     channel c fastest, so a pair is two consecutive input channels of one
+ *     pixel; an odd last channel has an implicit zero partner;
+ *   - for n < 4 a value whose partner is zero gets a 2n-bit window (Section
+ *     5.1, "total window sizes are 6 and 4 bits") whose allowed shifts are the
+ *     t for which both t and t+n are allowed n-bit shifts (the two n-bit
+ *     multipliers of Eq. 4 acting as the high and low half).
+ *
+ * Parity status: the tie direction, the saturate-versus-renormalise choice
+ * and the 2n-bit shift set are readings, not printed values -- they are
+ * "parity unpinned" against the authors' own code; everything else is pinned
+ * by the tests under tests/ (worked examples of Section 3.1, closed forms,
+ * an independently written second formulation, brute force, library conv).
+ */
+#ifndef SPARQ_ORACLE_H
+#define SPARQ_ORACLE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct {
+    int32_t  window_bits;   /* n = 4, 3, 2; 8 = layer left at plain 8 bits (Section 5, first conv) */
+    uint32_t shift_mask;    /* bit t set <=> window [t+n-1 : t] is a placement option              */
+    int32_t  round_nearest; /* 0 = plain trim, 1 = "+R"                                            */
+    int32_t  pair;          /* 1 = vSPARQ on, 0 = "-vS"                                            */
+} sparq_ref_mode;
+
+typedef struct {
+    int32_t B, H, W, C;          /* input  NHWC uint8                */
+    int32_t N, KH, KW;           /* weight [N][KH][KW][C] int8       */
+    int32_t stride_h, stride_w;
+    int32_t pad_h, pad_w;
+} sparq_ref_conv;
+
+/* 0 if the mode is usable, 1 otherwise. */
+int sparq_ref_mode_check(const sparq_ref_mode *mode);
+
+/* Shift set of the 2n-bit window granted to a value whose partner is zero. */
+uint32_t sparq_ref_wide_shift_mask(int32_t n, uint32_t shift_mask);
+
+/* bSPARQ on one value: returns the trimmed value q << s; *shift_out (may be
+ * NULL) receives s.  x in [0,255], n in [1,8]; S must cover bit 7. */
+int sparq_ref_trim_value(int x, int n, uint32_t S, int round_nearest, int *shift_out);
+
+/* vSPARQ + bSPARQ over rows of C contiguous channels. y may alias x. */
+int sparq_trim_ref(const uint8_t *x, uint8_t *y, int64_t rows, int32_t C,
+                   const sparq_ref_mode *mode);
+
+/* Trimmed convolution by definition.  If row_idx != NULL only the n_rows
+ * output rows m = row_idx[i] (m = (b*Ho + oy)*Wo + ox) are computed and
+ * stored densely as [n_rows][N]; otherwise all M rows (n_rows ignored).
+ * acc (int32) and out (double, = acc * scale[n]) may each be NULL.
+ * Returns 2 if an accumulator leaves the int32 range. */
+int sparq_conv_gemm_ref(const uint8_t *x, const int8_t *w,
+                        const sparq_ref_conv *desc, const sparq_ref_mode *mode,
+                        const int64_t *row_idx, int64_t n_rows,
+                        int32_t *acc, const float *scale, double *out);
+
+/* out[m][n] = (double)acc[m][n] * (double)scale[n] */
+int sparq_dequant_ref(const int32_t *acc, const float *scale, double *out,
+                      int64_t M, int32_t N);
+
+#ifdef __cplusplus
+}
+#endif
+#endif
