@@ -1,0 +1,126 @@
+/*
+ * libsparq -- SPARQ activation-trimmed convolution-as-GEMM for AMD MI355X (gfx950).
+ *
+ * SPARQ (post-training sparsity-aware quantisation) trims already-quantised
+ * uint8 activations on the fly:
+ *   bSPARQ (Section 3.1)  keeps an n-bit window placed at the leading one,
+ *          choosing the smallest allowed shift whose window reaches it,
+ *          either dropping the residual LSBs or rounding on them;
+ *   vSPARQ (Section 3.2, Eq. 1-2) looks at pairs of consecutive activations
+ *          of the dot product: if one is zero the other keeps the whole 2n-bit
+ *          budget (all 8 bits for n = 4), otherwise both go through bSPARQ.
+ * The trimmed value is q << s, i.e. an ordinary 8-bit integer, so Eq. 1 is
+ * evaluated as an int8 x int8 -> int32 contraction on the matrix cores, then
+ * dequantised with one fp32 factor per output channel (Section 5: per-layer
+ * activation scale times per-kernel weight scale).
+ *
+ * Conventions
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *     never allocates, frees or keeps a pointer after the call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = default stream).  All
+ *     entry points only enqueue work on that stream and return immediately.
+ *   - Structs passed by pointer are HOST memory, read during the call only.
+ *   - Layouts: activations uint8 NHWC [B][H][W][C]; weights int8
+ *     [N][KH][KW][C]; outputs row-major [M][N] with M = B*Ho*Wo, row
+ *     m = (b*Ho + oy)*Wo + ox; the dot-product index runs (kh, kw, c) with c
+ *     fastest, so a vSPARQ pair is two consecutive input channels (2j, 2j+1)
+ *     of one pixel; with odd C the last channel has an implicit zero partner.
+ *   - Errors are reported by return code only.  Arguments are validated on
+ *     the host before anything is enqueued; on an error nothing was launched.
+ *   - No global state; calls on different streams may overlap.
+ */
+#ifndef SPARQ_H
+#define SPARQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SPARQ_OK = 0,
+    SPARQ_EINVAL = 1,       /* null pointer, bad dimension, bad mode, misaligned buffer */
+    SPARQ_EUNSUPPORTED = 2, /* valid but outside what the kernels cover (e.g. tensor >= 2 GiB) */
+    SPARQ_EWORKSPACE = 3,   /* workspace / packed buffer smaller than required */
+    SPARQ_ELAUNCH = 4       /* the HIP runtime refused a launch */
+} sparq_status;
+
+/* How activations are trimmed.
+ *   window_bits   n: 4 (the paper's default), 3 or 2 (Section 5.1, Table 4);
+ *                 8 = leave the layer at plain 8 bits (the first convolution,
+ *                 Section 5) -- the other fields are then ignored.
+ *   shift_mask    bit t set <=> the window may sit at bits [t+n-1 : t].
+ *                 n = 4: 5opt 0x1F, 3opt 0x15, 2opt 0x11 (Section 3.1);
+ *                 n = 3: 6opt 0x3F; n = 2: 7opt 0x7F.  Must contain bit 0 and
+ *                 bit 8-n and nothing above; with pair = 1 and n < 4 the set
+ *                 {t : t and t+n allowed} of 2n-bit placements must contain 0
+ *                 and 8-2n.
+ *   round_nearest 0 = plain trim, 1 = round half up on the residual LSBs
+ *                 inside the chosen window, saturating at 2^n - 1 ("+R").
+ *   pair          1 = vSPARQ on, 0 = every value trimmed on its own ("-vS").
+ */
+typedef struct {
+    int32_t  window_bits;
+    uint32_t shift_mask;
+    int32_t  round_nearest;
+    int32_t  pair;
+} sparq_mode;
+
+/* A convolution (dilation 1, groups 1).  Ho = (H + 2*pad_h - KH)/stride_h + 1,
+ * Wo likewise.  A plain matrix product A[M][K] * W[N][K]^T is the case
+ * B = 1, H = M, W = 1, C = K, KH = KW = 1, stride 1, pad 0. */
+typedef struct {
+    int32_t B, H, W, C;
+    int32_t N, KH, KW;
+    int32_t stride_h, stride_w;
+    int32_t pad_h, pad_w;
+} sparq_conv_desc;
+
+/* Standalone trim (Sections 3.1-3.2): y[r][c] = trimmed x[r][c] for `rows`
+ * vectors of C contiguous channels; pairs are (2j, 2j+1) inside one vector.
+ * y may alias x exactly (in place); partial overlap is not allowed. */
+sparq_status sparq_trim(const uint8_t *x, uint8_t *y, int64_t rows, int32_t C,
+                        const sparq_mode *mode, void *stream);
+
+/* Size in bytes of the packed form of the weights of `desc` (0 if desc is invalid). */
+size_t sparq_packed_bytes(const sparq_conv_desc *desc);
+
+/* Reorders w [N][KH][KW][C] into the tile order the contraction kernel reads
+ * and stores sum_k w[n][k] per output channel (needed because activations
+ * enter the signed matrix instruction as x - 128).  Done once per layer; the
+ * packed buffer is read-only afterwards.  `packed` must be 256-byte aligned. */
+sparq_status sparq_pack_weights(const int8_t *w, const sparq_conv_desc *desc,
+                                void *packed, size_t packed_bytes, void *stream);
+
+/* Scratch the convolution needs for this descriptor and mode (0 for channel
+ * counts that are a multiple of 16; otherwise room for a trimmed, channel-padded
+ * copy of the input). */
+size_t sparq_workspace_bytes(const sparq_conv_desc *desc, const sparq_mode *mode);
+
+/* Eq. 1 over trimmed activations as an implicit GEMM:
+ *   acc[m][n] = sum_{kh,kw,c} T(x)[b, oy*stride_h - pad_h + kh, ox*stride_w - pad_w + kw, c] * w[n][kh][kw][c]
+ * (zero outside the image), exact in int32, and optionally
+ *   out[m][n] = (float)acc[m][n] * scale[n].
+ * At least one of acc / out must be given; out requires scale.  x must be
+ * 16-byte aligned, acc/out 16-byte aligned, packed_w as produced by
+ * sparq_pack_weights for the same desc.  workspace may be NULL when
+ * sparq_workspace_bytes() is 0.  Rejected with SPARQ_EINVAL when K = KH*KW*C
+ * is large enough for 255*127*K to leave the int32 range. */
+sparq_status sparq_conv_gemm(const uint8_t *x, const void *packed_w,
+                             const sparq_conv_desc *desc, const sparq_mode *mode,
+                             int32_t *acc, const float *scale, float *out,
+                             void *workspace, size_t workspace_bytes, void *stream);
+
+/* Per-output-channel dequantisation (Section 5): out[m][n] = (float)acc[m][n] * scale[n]. */
+sparq_status sparq_dequant(const int32_t *acc, const float *scale, float *out,
+                           int64_t M, int32_t N, void *stream);
+
+/* Static description of a status code. */
+const char *sparq_strerror(sparq_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPARQ_H */

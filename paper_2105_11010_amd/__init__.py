@@ -1,0 +1,14 @@
+"""SPARQ trimmed convolution-as-GEMM on AMD MI355X (gfx950).
+
+Thin Python front end of ``libsparq.so`` (see ``include/sparq.h``): the names
+below are the C entry points, taking torch device tensors as plain buffers.
+"""
+from .binding import (  # noqa: F401
+    LIB_PATH, SparqConvDesc, SparqError, SparqMode, conv_desc, lib, mode, out_rows, strerror,
+    sparq_conv_gemm, sparq_dequant, sparq_pack_weights, sparq_packed_bytes, sparq_trim,
+    sparq_workspace_bytes,
+)
+
+__all__ = ["LIB_PATH", "SparqConvDesc", "SparqError", "SparqMode", "conv_desc", "lib", "mode", "out_rows",
+           "strerror", "sparq_conv_gemm", "sparq_dequant", "sparq_pack_weights", "sparq_packed_bytes",
+           "sparq_trim", "sparq_workspace_bytes"]

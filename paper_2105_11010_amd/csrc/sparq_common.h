@@ -1,0 +1,112 @@
+// Host-side helpers shared by the translation units of libsparq: argument
+// validation, the packed-weight layout and launch bookkeeping.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/sparq.h"
+#include "sparq_swar.h"
+
+namespace sparq {
+
+constexpr int kChunk = 16;        // bytes one lane feeds to an int8 matrix instruction
+constexpr int kStepK = 64;        // reduction bytes per main-loop step
+constexpr int kPadN = 256;        // packed output channels are padded to this
+
+inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+
+// ---- mode -----------------------------------------------------------------
+inline bool mode_valid(const sparq_mode* m) {
+    if (!m) return false;
+    const int n = m->window_bits;
+    if (n == 8) return true;
+    if (n != 2 && n != 3 && n != 4) return false;
+    const uint32_t S = m->shift_mask;
+    if (S >> (8 - n + 1)) return false;
+    if (!(S & 1u) || !((S >> (8 - n)) & 1u)) return false;
+    if ((m->round_nearest | 1) != 1 || (m->pair | 1) != 1) return false;
+    if (m->pair) {
+        const uint32_t W = wide_shift_mask(n, S);
+        if (!(W & 1u) || !((W >> (8 - 2 * n)) & 1u)) return false;
+    }
+    return true;
+}
+
+// Which compiled variant of the trim a mode needs.
+enum TrimKind : int {
+    kTrimNone = 0,
+    kTrimFloor, kTrimFloorPair, kTrimFloorPairWide,
+    kTrimRound, kTrimRoundPair, kTrimRoundPairWide,
+    kTrimKinds
+};
+
+inline TrimKind trim_kind(const sparq_mode* m) {
+    if (m->window_bits == 8) return kTrimNone;
+    const bool wide = m->pair && m->window_bits < 4;
+    if (m->round_nearest) return !m->pair ? kTrimRound : (wide ? kTrimRoundPairWide : kTrimRoundPair);
+    return !m->pair ? kTrimFloor : (wide ? kTrimFloorPairWide : kTrimFloorPair);
+}
+
+template <int KIND>
+__device__ __forceinline__ uint32_t trim4_kind(uint32_t x, const TrimLuts& L) {
+    if constexpr (KIND == kTrimNone) return x;
+    else if constexpr (KIND == kTrimFloor) return trim4<false, false, false>(x, L);
+    else if constexpr (KIND == kTrimFloorPair) return trim4<false, true, false>(x, L);
+    else if constexpr (KIND == kTrimFloorPairWide) return trim4<false, true, true>(x, L);
+    else if constexpr (KIND == kTrimRound) return trim4<true, false, false>(x, L);
+    else if constexpr (KIND == kTrimRoundPair) return trim4<true, true, false>(x, L);
+    else return trim4<true, true, true>(x, L);
+}
+
+// ---- convolution geometry and packed weights --------------------------------
+struct ConvGeom {
+    int B, H, W, C, N, KH, KW, sh, sw, ph, pw;
+    int Ho, Wo;
+    int64_t M;
+    int Cp;          // channels padded to a multiple of 16 (what the kernel sees)
+    int K;           // KH*KW*C   (the method's dot-product length)
+    int Kk;          // KH*KW*Cp  (what the kernel contracts over)
+    int Kp;          // Kk padded to kStepK
+    int Np;          // N padded to kPadN
+    size_t w_off;    // byte offset of the weight tiles inside the packed buffer
+    size_t packed_bytes;
+    size_t x_bytes;
+};
+
+inline bool conv_geom(const sparq_conv_desc* d, ConvGeom* g) {
+    if (!d) return false;
+    if (d->B <= 0 || d->H <= 0 || d->W <= 0 || d->C <= 0 || d->N <= 0 || d->KH <= 0 || d->KW <= 0 ||
+        d->stride_h <= 0 || d->stride_w <= 0 || d->pad_h < 0 || d->pad_w < 0)
+        return false;
+    if ((int64_t)d->H + 2 * (int64_t)d->pad_h < d->KH || (int64_t)d->W + 2 * (int64_t)d->pad_w < d->KW) return false;
+    g->B = d->B; g->H = d->H; g->W = d->W; g->C = d->C; g->N = d->N; g->KH = d->KH; g->KW = d->KW;
+    g->sh = d->stride_h; g->sw = d->stride_w; g->ph = d->pad_h; g->pw = d->pad_w;
+    g->Ho = (d->H + 2 * d->pad_h - d->KH) / d->stride_h + 1;
+    g->Wo = (d->W + 2 * d->pad_w - d->KW) / d->stride_w + 1;
+    g->M = (int64_t)d->B * g->Ho * g->Wo;
+    const int64_t K = (int64_t)d->KH * d->KW * d->C;
+    // 255 * 127 * K must stay inside int32 (it also bounds the offset form 128 * 127 * K)
+    if (K * 255 * 127 > 2147483647LL) return false;
+    g->K = (int)K;
+    g->Cp = (int)round_up(d->C, kChunk);
+    const int64_t Kk = (int64_t)d->KH * d->KW * g->Cp;
+    if (Kk > (1 << 24)) return false;
+    g->Kk = (int)Kk;
+    g->Kp = (int)round_up(Kk, kStepK);
+    g->Np = (int)round_up(d->N, kPadN);
+    g->w_off = (size_t)round_up((int64_t)g->Np * 4, 256);
+    g->packed_bytes = g->w_off + (size_t)g->Kp * (size_t)g->Np;
+    g->x_bytes = (size_t)d->B * d->H * d->W * (size_t)d->C;
+    return true;
+}
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+inline sparq_status launch_status() { return hipGetLastError() == hipSuccess ? SPARQ_OK : SPARQ_ELAUNCH; }
+
+// Implemented in sparq_elementwise.hip: trimmed copy of x with channels padded to Cp.
+sparq_status launch_trim_pad(const uint8_t* x, uint8_t* xp, int64_t pixels, int C, int Cp,
+                             const sparq_mode* mode, hipStream_t stream);
+
+}  // namespace sparq

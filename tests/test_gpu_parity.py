@@ -1,0 +1,189 @@
+"""GPU parity: libsparq (HIP, through the C ABI) against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+import torch
+
+import sparq_synth as S
+
+pytestmark = pytest.mark.gpu
+
+MODES_N4 = [S.Mode(4, m, r, p) for m in (S.OPT5, S.OPT3, S.OPT2) for r in (0, 1) for p in (0, 1)]
+MODES_LOW = [S.Mode(2, S.OPT7_2B, r, p) for r in (0, 1) for p in (0, 1)] + \
+            [S.Mode(3, S.OPT6_3B, r, p) for r in (0, 1) for p in (0, 1)]
+MODES_ODD = [S.Mode(4, 0x1B, 1, 1), S.Mode(4, 0x13, 0, 1), S.Mode(3, 0x2D, 1, 1), S.Mode(2, 0x5F, 1, 1), S.PLAIN8]
+
+
+@pytest.fixture(scope="module")
+def sq():
+    assert torch.cuda.is_available(), "GPU tests need a device"
+    import paper_2105_11010_amd as sq_
+    return sq_
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def run_conv(sq, x, w, sc, layer, mode, want_acc=True, want_out=True):
+    d = sq.conv_desc(layer.B, layer.H, layer.W, layer.C, layer.N, layer.KH, layer.KW, layer.stride, layer.pad)
+    m = sq.mode(*mode.astuple())
+    xd, wd, sd = dev(x), dev(w), dev(sc)
+    packed = torch.empty(sq.sparq_packed_bytes(d), dtype=torch.uint8, device="cuda:0")
+    sq.sparq_pack_weights(wd, d, packed)
+    wsb = sq.sparq_workspace_bytes(d, m)
+    ws = torch.empty(wsb, dtype=torch.uint8, device="cuda:0") if wsb else None
+    acc = torch.full((layer.M, layer.N), -7, dtype=torch.int32, device="cuda:0") if want_acc else None
+    out = torch.full((layer.M, layer.N), -7.0, dtype=torch.float32, device="cuda:0") if want_out else None
+    sq.sparq_conv_gemm(xd, packed, d, m, acc=acc, scale=sd if want_out else None, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    return (acc.cpu().numpy() if want_acc else None), (out.cpu().numpy() if want_out else None)
+
+
+def check_layer(sq, oracle, layer, mode, seed_cfg=8, rows=None):
+    x, w, sc = S.gen_layer(seed_cfg, layer)
+    acc, out = run_conv(sq, x, w, sc, layer, mode)
+    ref_acc, ref_out = oracle.conv_gemm(x, w, layer.stride, layer.pad, scale=sc, rows=rows, **mode.kwargs())
+    if rows is not None:
+        acc, out = acc[rows], out[rows]
+    assert np.array_equal(acc, ref_acc), f"{layer.name} {mode.label}: int32 mismatch"
+    # fp32 dequantised output within 1e-6 relative of the fp64 oracle
+    err = np.abs(out.astype(np.float64) - ref_out)
+    assert np.all(err <= 1e-6 * np.abs(ref_out)), f"{layer.name} {mode.label}: fp32 output off"
+
+
+# ---------------------------------------------------------------- trim ------
+
+@pytest.mark.parametrize("mode", MODES_N4 + MODES_LOW + MODES_ODD, ids=lambda m: m.label + f"-{m.shift_mask:#x}")
+def test_trim_all_pairs(sq, oracle, mode):
+    """All 256 x 256 activation pairs, in both byte lanes of the packed word."""
+    a, b = np.meshgrid(np.arange(256, dtype=np.uint8), np.arange(256, dtype=np.uint8), indexing="ij")
+    x = np.stack([a, b, b, a], axis=-1).reshape(-1, 4)
+    xd = dev(x)
+    y = torch.empty_like(xd)
+    sq.sparq_trim(xd, y, sq.mode(*mode.astuple()))
+    torch.cuda.synchronize()
+    assert np.array_equal(y.cpu().numpy(), oracle.trim(x, **mode.kwargs()))
+
+
+@pytest.mark.parametrize("C", [1, 2, 3, 6, 7, 16, 30, 33, 64, 159])
+@pytest.mark.parametrize("mode", [S.Mode(4, S.OPT5, 1, 1), S.Mode(4, S.OPT3, 0, 1), S.Mode(2, S.OPT7_2B, 1, 1)],
+                         ids=lambda m: m.label)
+def test_trim_row_lengths(sq, oracle, C, mode):
+    """Odd and ragged channel counts: the last channel of an odd row has no partner."""
+    rng = S.rng_for(8, 100 + C)
+    for rows in (1, 5, 1031):
+        x = S.gen_activations((rows, C), 0.5, rng)
+        xd = dev(x)
+        y = torch.empty_like(xd)
+        sq.sparq_trim(xd, y, sq.mode(*mode.astuple()))
+        torch.cuda.synchronize()
+        assert np.array_equal(y.cpu().numpy(), oracle.trim(x, **mode.kwargs())), (rows, C)
+
+
+def test_trim_in_place_large_and_empty(sq, oracle):
+    mode = S.Mode(4, S.OPT5, 1, 1)
+    x = S.gen_activations((4099, 96), 0.5, S.rng_for(8, 200))
+    xd = dev(x)
+    sq.sparq_trim(xd, xd, sq.mode(*mode.astuple()))
+    torch.cuda.synchronize()
+    assert np.array_equal(xd.cpu().numpy(), oracle.trim(x, **mode.kwargs()))
+    e = torch.empty((0, 8), dtype=torch.uint8, device="cuda:0")
+    sq.sparq_trim(e, e, sq.mode(*mode.astuple()))
+
+
+# ------------------------------------------------------------- dequant ------
+
+@pytest.mark.parametrize("M,N", [(1, 1), (37, 19), (513, 64), (1000, 160)])
+def test_dequant(sq, oracle, M, N):
+    rng = S.rng_for(8, 300 + N)
+    acc = rng.integers(-2 ** 31, 2 ** 31, size=(M, N), dtype=np.int64).astype(np.int32)
+    sc = S.gen_scales(N, rng)
+    out = torch.empty((M, N), dtype=torch.float32, device="cuda:0")
+    sq.sparq_dequant(dev(acc), dev(sc), out)
+    torch.cuda.synchronize()
+    ref = oracle.dequant(acc, sc)
+    err = np.abs(out.cpu().numpy().astype(np.float64) - ref)
+    assert np.all(err <= 1e-6 * np.abs(ref))
+
+
+# ---------------------------------------------------------- conv / gemm -----
+
+def test_config0_full(sq, oracle):
+    (layer,) = S.config0()
+    x, w, sc = S.gen_layer(0, layer)
+    acc, out = run_conv(sq, x, w, sc, layer, layer.mode)
+    ref_acc, ref_out = oracle.conv_gemm(x, w, layer.stride, layer.pad, scale=sc, **layer.mode.kwargs())
+    assert np.array_equal(acc, ref_acc)
+    assert np.all(np.abs(out.astype(np.float64) - ref_out) <= 1e-6 * np.abs(ref_out))
+
+
+SHAPES = [
+    # name, B, H, W, C, N, KH, KW, stride, pad
+    S.ConvLayer("gemm_small", 1, 300, 1, 64, 32),
+    S.ConvLayer("gemm_ragged", 1, 777, 1, 208, 100),
+    S.ConvLayer("gemm_k16", 1, 130, 1, 16, 8),
+    S.ConvLayer("gemm_k48_n3", 1, 129, 1, 48, 3),
+    S.ConvLayer("1x1_s2", 3, 15, 13, 32, 40, 1, 1, (2, 2), (0, 0)),
+    S.ConvLayer("3x3_p1", 2, 13, 11, 32, 24, 3, 3, (1, 1), (1, 1)),
+    S.ConvLayer("3x3_s2_p1", 2, 17, 19, 48, 36, 3, 3, (2, 2), (1, 1)),
+    S.ConvLayer("3x3_s2_p0", 1, 17, 17, 96, 20, 3, 3, (2, 2), (0, 0)),
+    S.ConvLayer("5x5_p2", 1, 12, 12, 48, 64, 5, 5, (1, 1), (2, 2)),
+    S.ConvLayer("1x7", 2, 9, 17, 32, 33, 1, 7, (1, 1), (0, 3)),
+    S.ConvLayer("7x1", 2, 17, 9, 160, 17, 7, 1, (1, 1), (3, 0)),
+    S.ConvLayer("odd_c65", 1, 10, 10, 65, 12, 3, 3, (1, 1), (1, 1)),
+    S.ConvLayer("odd_c3_7x7", 2, 20, 20, 3, 16, 7, 7, (2, 2), (3, 3)),
+    S.ConvLayer("odd_c159_n161", 1, 6, 17, 159, 161, 1, 7, (1, 1), (0, 3)),
+    S.ConvLayer("wide_n", 1, 140, 1, 128, 520),
+]
+
+
+@pytest.mark.parametrize("layer", SHAPES, ids=lambda l: l.name)
+@pytest.mark.parametrize("mode", [S.Mode(4, S.OPT5, 1, 1), S.Mode(4, S.OPT3, 0, 1), S.Mode(2, S.OPT7_2B, 1, 1), S.PLAIN8],
+                         ids=lambda m: m.label)
+def test_conv_shapes(sq, oracle, layer, mode):
+    check_layer(sq, oracle, layer, mode, seed_cfg=8)
+
+
+@pytest.mark.parametrize("mode", MODES_N4 + MODES_LOW + MODES_ODD, ids=lambda m: m.label + f"-{m.shift_mask:#x}")
+def test_conv_all_modes(sq, oracle, mode):
+    check_layer(sq, oracle, S.ConvLayer("3x3_modes", 1, 14, 14, 64, 48, 3, 3, (1, 1), (1, 1), index=3), mode)
+
+
+def test_extreme_values(sq, oracle):
+    """Saturation and accumulator extremes: all-255 / all-zero activations, all -127 / +127 weights, K = 4608."""
+    layer = S.ConvLayer("extreme", 1, 70, 1, 4608, 8)
+    sc = np.full(8, 0.005, dtype=np.float32)
+    for xv in (255, 0, 128):
+        for wv in (-127, 127):
+            x = np.full(layer.x_shape(), xv, dtype=np.uint8)
+            w = np.full(layer.w_shape(), wv, dtype=np.int8)
+            for mode in (S.Mode(4, S.OPT5, 1, 1), S.PLAIN8):
+                acc, _ = run_conv(sq, x, w, sc, layer, mode)
+                ref, _ = oracle.conv_gemm(x, w, **mode.kwargs())
+                assert np.array_equal(acc, ref)
+
+
+def test_only_out_or_only_acc(sq, oracle):
+    layer = S.ConvLayer("3x3_outs", 1, 9, 9, 32, 16, 3, 3, (1, 1), (1, 1))
+    mode = S.Mode(4, S.OPT5, 1, 1)
+    x, w, sc = S.gen_layer(8, layer)
+    ref_acc, ref_out = oracle.conv_gemm(x, w, layer.stride, layer.pad, scale=sc, **mode.kwargs())
+    acc, _ = run_conv(sq, x, w, sc, layer, mode, want_acc=True, want_out=False)
+    assert np.array_equal(acc, ref_acc)
+    _, out = run_conv(sq, x, w, sc, layer, mode, want_acc=False, want_out=True)
+    assert np.all(np.abs(out.astype(np.float64) - ref_out) <= 1e-6 * np.abs(ref_out))
+
+
+def test_fused_equals_trim_then_plain(sq):
+    """GPU-internal cross-check: trimming with the standalone kernel and contracting at plain
+    8 bits gives the same accumulators as the fused kernel."""
+    layer = S.ConvLayer("3x3_x", 2, 12, 12, 64, 40, 3, 3, (1, 1), (1, 1))
+    mode = S.Mode(4, S.OPT3, 1, 1)
+    x, w, sc = S.gen_layer(8, layer)
+    fused, _ = run_conv(sq, x, w, sc, layer, mode, want_out=False)
+    xd = dev(x)
+    y = torch.empty_like(xd)
+    sq.sparq_trim(xd, y, sq.mode(*mode.astuple()))
+    torch.cuda.synchronize()
+    plain, _ = run_conv(sq, y.cpu().numpy(), w, sc, layer, S.PLAIN8, want_out=False)
+    assert np.array_equal(fused, plain)
