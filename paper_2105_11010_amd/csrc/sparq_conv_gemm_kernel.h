@@ -1,0 +1,346 @@
+// Fused SPARQ convolution-as-GEMM for gfx950.
+//
+//   acc[m][n] = sum_k T(x)[m, k] * w[n][k]          (Eq. 1 over trimmed activations)
+//
+// The im2col matrix is never materialised: every workgroup gathers its
+// activation tile straight from the NHWC tensor with 128-bit loads (one load =
+// 16 consecutive channels of one pixel = 8 vSPARQ pairs inside one lane), trims
+// the four packed words in registers (sparq_swar.h), flips them to signed
+// (x - 128, a single xor) and stages them in LDS, from where all wavefronts of
+// the workgroup read them.  Weights are pre-packed in matrix-instruction
+// fragment order and go from L2 straight into registers.  The contraction runs
+// on v_mfma_i32_32x32x32_i8; the epilogue adds back 128 * sum_k w[n][k], which
+// makes the result exact in int32, and optionally applies the per-channel
+// dequantisation factor (Section 5).
+//
+// This mirrors the paper's placement of the trimming unit in front of the
+// array (Section 5: it runs at a much lower rate than the multipliers): an
+// activation is trimmed once when its tile is loaded and then reused for all
+// output channels the workgroup covers.
+#pragma once
+#include "sparq_common.h"
+
+namespace sparq {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+
+struct GemmParams {
+    const uint8_t* x;        // activations, NHWC with C a multiple of 16
+    const uint8_t* wpk;      // packed weight tiles
+    const int32_t* colsum;   // sum_k w[n][k], Np entries
+    int32_t* acc;            // [M][N] or null
+    const float* scale;      // [N] or null
+    float* out;              // [M][N] or null
+    int64_t M;
+    uint32_t x_bytes;
+    int N, Np, Kk, nkb;
+    int H, W, C, Ho, Wo, KH, KW, sh, sw, ph, pw;
+    int tiles_m, tiles_n;
+    float rcp_c, rcp_kw;     // 1/C and 1/KW for the branch-free reduction-index decode
+    TrimLuts luts;
+};
+
+constexpr uint32_t kInvalidOffset = 0x80000000u;   // beyond any buffer this kernel accepts (< 2 GiB)
+
+constexpr int gcd2(int a, int b) { return b == 0 ? a : gcd2(b, a % b); }
+constexpr int lcm3(int a, int b, int c) { int l = a / gcd2(a, b) * b; return l / gcd2(l, c) * c; }
+
+// Tile shape: TM output pixels x TN output channels per workgroup, WGM x WGN
+// wavefronts.  PA / PB: how many reduction steps ahead of their consumption the
+// activation / weight loads are issued.
+template <int TM, int TN, int WGM, int WGN, int PA, int PB>
+struct TileCfg {
+    static constexpr int kTM = TM, kTN = TN, kWGM = WGM, kWGN = WGN, kPA = PA, kPB = PB;
+    static constexpr int kThreads = 64 * WGM * WGN;
+    static constexpr int kWTM = TM / WGM, kWTN = TN / WGN;      // per-wavefront tile
+    static constexpr int kFM = kWTM / 32, kFN = kWTN / 32;      // 32x32 fragments per wavefront
+    static constexpr int kAChunks = TM * 4 / kThreads;          // 16-byte activation loads per lane per step
+    // Only activations go through LDS (they are trimmed once and shared by all
+    // wavefronts); every wavefront reads its own weight fragments straight from the
+    // packed buffer.  A stage holds four 16-byte-chunk planes, [plane][row][16]; planes
+    // are padded by 64 bytes so that the four lanes that write one row's 64 bytes (one
+    // chunk each, into four different planes) land on different banks.
+    static constexpr int kPlaneA = TM * kChunk + 64;
+    static constexpr int kLdsA = 4 * kPlaneA;                   // bytes per stage
+    static constexpr int kStages = 3;                           // written two steps ahead, read one step ahead
+    static constexpr int kLdsBytes = kStages * kLdsA;
+    static constexpr int kUnroll = lcm3(2, PA, PB);             // main-loop unroll: every ring index compile-time
+    static constexpr int kWgPerCu = (kFM * kFN * 16 <= 64) ? 2 : 1;    // small accumulators: two workgroups per CU
+    static_assert(TM % (32 * WGM) == 0 && TN % (32 * WGN) == 0, "tile must split into 32x32 fragments");
+    static_assert((TM * 4) % kThreads == 0, "activation loads must divide evenly");
+    static_assert(PA >= 1 && PA <= 4 && PB >= 1 && PB <= 4, "prefetch depth");
+    static_assert(kUnroll % 2 == 0 && kUnroll % PA == 0 && kUnroll % PB == 0, "unroll must cover all rings");
+};
+
+template <class Cfg, int KIND>
+__global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256) void conv_gemm_kernel(const GemmParams p) {
+    constexpr int TM = Cfg::kTM, NT = Cfg::kThreads, PA = Cfg::kPA, PB = Cfg::kPB, U = Cfg::kUnroll;
+    constexpr int FM = Cfg::kFM, FN = Cfg::kFN, AC = Cfg::kAChunks;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];   // [3][4][TM (+pad)][16]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave % Cfg::kWGM, wn = wave / Cfg::kWGM;
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const int kc = tid & 3;                  // which 16-byte chunk of a row's 64-byte step this lane gathers
+    const int nkb = p.nkb;
+    const __amdgpu_buffer_rsrc_t xrsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.x), 0, (int)p.x_bytes, 0x00020000);
+    const int ntiles = p.tiles_m * p.tiles_n;
+
+    // Persistent workgroups: each one walks over tiles blockIdx.x, blockIdx.x + gridDim.x, ...
+    // so that the result stores of one tile drain while the next tile's loads and matrix
+    // instructions already run.  The output-channel tile is the fast index: consecutive
+    // tile numbers share their activation rows.
+    for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int tile_n = tile % p.tiles_n;
+        const int tile_m = tile / p.tiles_n;
+        const int64_t m0 = (int64_t)tile_m * TM;
+        const int n0 = tile_n * Cfg::kTN;
+
+        // ---- activation gather bookkeeping (fixed per lane and tile) ----
+        int32_t row_base[AC];                    // byte offset of (b, oy*sh-ph, ox*sw-pw, 0)
+        int32_t row_iy[AC], row_ix[AC];
+#pragma unroll
+        for (int i = 0; i < AC; ++i) {
+            int64_t m = m0 + (tid >> 2) + i * (NT / 4);
+            if (m >= p.M) m = p.M - 1;
+            const int ox = (int)(m % p.Wo);
+            const int64_t t = m / p.Wo;
+            const int oy = (int)(t % p.Ho);
+            const int b = (int)(t / p.Ho);
+            const int iy0 = oy * p.sh - p.ph, ix0 = ox * p.sw - p.pw;
+            row_iy[i] = iy0;
+            row_ix[i] = ix0;
+            row_base[i] = (int32_t)((((int64_t)b * p.H + iy0) * p.W + ix0) * p.C);
+        }
+
+        // Everything inside the main loop is branch-free so that the loop body stays one
+        // basic block and outstanding loads can be waited on exactly.  Steps past the end
+        // request out-of-range activations (returned as zeros) and re-read the last weight
+        // step; they are staged but never multiplied.
+        int a_step = 0;                          // next activation step to request
+        auto load_a = [&](v4u (&ar)[AC]) {
+            // where this lane's 16 bytes sit in the (kh, kw, c) reduction index
+            const int k = a_step * kStepK + kc * kChunk;
+            int tap = (int)((float)k * p.rcp_c);
+            int c0 = k - tap * p.C;
+            tap += (c0 >= p.C) - (c0 < 0);
+            c0 = k - tap * p.C;
+            int kh = (int)((float)tap * p.rcp_kw);
+            int kw = tap - kh * p.KW;
+            kh += (kw >= p.KW) - (kw < 0);
+            kw = tap - kh * p.KW;
+            const bool k_ok = k < p.Kk;          // false in the zero-padded K tail and past the end
+            const int32_t tap_off = (kh * p.W + kw) * p.C + c0;
+#pragma unroll
+            for (int i = 0; i < AC; ++i) {
+                const bool ok = k_ok & ((unsigned)(row_iy[i] + kh) < (unsigned)p.H) &
+                                ((unsigned)(row_ix[i] + kw) < (unsigned)p.W);
+                const uint32_t off = ok ? (uint32_t)(row_base[i] + tap_off) : kInvalidOffset;
+                ar[i] = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, (int)off, 0, 0);   // out of range reads 0
+            }
+            ++a_step;
+        };
+
+        // trim + flip to signed + stage in LDS
+        auto store_a = [&](int stage, const v4u (&ar)[AC]) {
+            uint8_t* sa = lds + stage * Cfg::kLdsA + kc * Cfg::kPlaneA + (tid >> 2) * kChunk;
+#pragma unroll
+            for (int i = 0; i < AC; ++i) {
+                v4u v = ar[i];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[j] = trim4_kind<KIND>(v[j], p.luts) ^ 0x80808080u;
+                *reinterpret_cast<v4u*>(sa + i * (NT / 4) * kChunk) = v;
+            }
+        };
+
+        // weight fragments: lane (l32, lhi) of fragment j, half ks holds
+        // w[n0 + wn*WTN + j*32 + l32][k = 16*(2*ks + lhi) .. +15]
+        const uint8_t* wsrc = p.wpk + ((size_t)lhi * p.Np + n0 + wn * Cfg::kWTN + l32) * kChunk;
+        const size_t w_half = (size_t)2 * p.Np * kChunk;      // bytes between the two 32-wide halves of a step
+        int b_step = 0;
+        auto load_b = [&](v4i (&br)[FN], int ks) {
+#pragma unroll
+            for (int j = 0; j < FN; ++j) br[j] = *reinterpret_cast<const v4i*>(wsrc + ks * w_half + j * 32 * kChunk);
+        };
+        auto advance_b = [&]() {
+            ++b_step;
+            wsrc += (b_step < nkb) ? 2 * w_half : 0;
+        };
+
+        auto load_frags = [&](int stage, v4i (&af)[2][FM]) {
+            const uint8_t* sa = lds + stage * Cfg::kLdsA + (wm * Cfg::kWTM + l32) * kChunk + lhi * Cfg::kPlaneA;
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                for (int i = 0; i < FM; ++i)
+                    af[ks][i] = *reinterpret_cast<const v4i*>(sa + ks * 2 * Cfg::kPlaneA + i * 32 * kChunk);
+        };
+
+        v16i c[FM][FN];
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) c[i][j][v] = 0;
+
+        v4u a_reg[PA][AC];            // activation loads in flight
+        v4i b_reg[PB][2][FN];         // weight fragments in flight / in use
+        v4i a_frag[2][2][FM];         // activation fragments: [current / next step][half][fragment]
+
+        // ---- prologue ----
+        // Activations of step s are requested at step s-1-PA, staged in LDS at s-2, read into
+        // fragments at s-1 and multiplied at s; weights of step s are requested at s-PB.
+        // Ring slots: activations of step s in a_reg[s % PA], weights in b_reg[s % PB].
+        {
+            v4u a0[AC], a1[AC];
+            load_a(a0);
+            load_a(a1);
+#pragma unroll
+            for (int s = 2; s <= PA; ++s) load_a(a_reg[s % PA]);       // steps 2 .. PA
+#pragma unroll
+            for (int u = 0; u < PB; ++u) {                             // steps 0 .. PB-1
+                load_b(b_reg[u][0], 0);
+                load_b(b_reg[u][1], 1);
+                advance_b();
+            }
+            store_a(0, a0);
+            store_a(1, a1);
+        }
+        __syncthreads();
+        load_frags(0, a_frag[0]);
+
+        // One reduction step, in two scheduling regions the compiler may not move code
+        // across (otherwise it sinks the global loads next to their uses to save registers,
+        // which serialises memory latency with the matrix instructions):
+        //   first half : fragments of step kb+1 from LDS, request activations of step
+        //                kb+1+PA, multiply half 0, request weights of step kb+PB (half 0);
+        //   second half: trim and stage the activations of step kb+2, multiply half 1,
+        //                request weights of step kb+PB (half 1).
+        // The activations are the matrix instruction's row operand, so a lane ends up with
+        // one output channel (column l32) of 16 output pixels per fragment.
+        auto body = [&](int kb, v4i (&cur)[2][FM], v4i (&nxt)[2][FM], v4u (&a_new)[AC], const v4u (&a_old)[AC],
+                        v4i (&br)[2][FN]) {
+            const int st = kb % 3;                  // LDS stage of step kb
+            const int st1 = st == 2 ? 0 : st + 1;   // ... of step kb+1 (complete since the last barrier)
+            const int st2 = st1 == 2 ? 0 : st1 + 1; // ... of step kb+2 (free since the last barrier)
+            load_frags(st1, nxt);
+            load_a(a_new);
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+                    c[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur[0][i], br[0][j], c[i][j], 0, 0, 0);
+            load_b(br[0], 0);
+            __builtin_amdgcn_sched_barrier(0);
+            store_a(st2, a_old);
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+                    c[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur[1][i], br[1][j], c[i][j], 0, 0, 0);
+            load_b(br[1], 1);
+            advance_b();
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+        };
+
+        const int nfull = nkb / U * U;
+        for (int kb0 = 0; kb0 < nfull; kb0 += U) {
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                body(kb0 + u, a_frag[u & 1], a_frag[(u & 1) ^ 1], a_reg[(u + 1 + PA) % PA], a_reg[(u + 2) % PA],
+                     b_reg[u % PB]);
+        }
+#pragma unroll
+        for (int u = 0; u < U - 1; ++u)
+            if (nfull + u < nkb)
+                body(nfull + u, a_frag[u & 1], a_frag[(u & 1) ^ 1], a_reg[(u + 1 + PA) % PA], a_reg[(u + 2) % PA],
+                     b_reg[u % PB]);
+
+        // ---- epilogue: undo the -128 offset, store int32 and/or dequantised fp32 ----
+        // Register v of fragment (i, j) is pixel 8*(v/4) + 4*lhi + v%4, channel l32: each store
+        // instruction writes two full 128-byte runs of consecutive channels.
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+            const int n = n0 + wn * Cfg::kWTN + j * 32 + l32;
+            if (n >= p.N) continue;
+            const int32_t corr = 128 * p.colsum[n];
+            const float sc = p.out ? p.scale[n] : 0.0f;
+#pragma unroll
+            for (int i = 0; i < FM; ++i) {
+                const int64_t mb = m0 + wm * Cfg::kWTM + i * 32 + 4 * lhi;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int64_t m = mb + 8 * (v / 4) + (v % 4);
+                    if (m >= p.M) continue;
+                    const int32_t r = c[i][j][v] + corr;
+                    const int64_t o = m * p.N + n;
+                    if (p.acc) p.acc[o] = r;
+                    if (p.out) p.out[o] = __fmul_rn((float)r, sc);
+                }
+            }
+        }
+    }   // tile loop
+}
+
+// Number of compute units of the current device (queried once).
+inline int device_cu_count() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 256;
+        cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    }
+    return cus;
+}
+
+template <class Cfg, int KIND>
+sparq_status launch_cfg(const GemmParams& p, hipStream_t s) {
+    static bool attr_set = false;
+    auto kern = conv_gemm_kernel<Cfg, KIND>;
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                Cfg::kLdsBytes) != hipSuccess)
+            return SPARQ_ELAUNCH;
+        attr_set = true;
+    }
+    GemmParams q = p;
+    q.tiles_m = (int)((p.M + Cfg::kTM - 1) / Cfg::kTM);
+    q.tiles_n = (p.N + Cfg::kTN - 1) / Cfg::kTN;
+    const int64_t tiles = (int64_t)q.tiles_m * q.tiles_n;
+    if (tiles > 0x7FFFFFFF) return SPARQ_EUNSUPPORTED;
+    const int64_t resident = (int64_t)device_cu_count() * Cfg::kWgPerCu;
+    const unsigned blocks = (unsigned)(tiles < resident ? tiles : resident);
+    kern<<<blocks, Cfg::kThreads, Cfg::kLdsBytes, s>>>(q);
+    return launch_status();
+}
+
+template <class Cfg>
+sparq_status launch_kind(TrimKind kind, const GemmParams& p, hipStream_t s) {
+    switch (kind) {
+        case kTrimNone: return launch_cfg<Cfg, kTrimNone>(p, s);
+        case kTrimFloor: return launch_cfg<Cfg, kTrimFloor>(p, s);
+        case kTrimFloorPair: return launch_cfg<Cfg, kTrimFloorPair>(p, s);
+        case kTrimFloorPairWide: return launch_cfg<Cfg, kTrimFloorPairWide>(p, s);
+        case kTrimRound: return launch_cfg<Cfg, kTrimRound>(p, s);
+        case kTrimRoundPair: return launch_cfg<Cfg, kTrimRoundPair>(p, s);
+        default: return launch_cfg<Cfg, kTrimRoundPairWide>(p, s);
+    }
+}
+
+// One translation unit per tile shape (sparq_conv_gemm_tile*.hip) instantiates the
+// kernel for every trim variant and exports a launcher with this signature.
+typedef sparq_status (*TileLauncher)(TrimKind, const GemmParams&, hipStream_t);
+#define SPARQ_DECLARE_TILE(name) sparq_status name(TrimKind kind, const GemmParams& p, hipStream_t s)
+SPARQ_DECLARE_TILE(launch_tile_128x128_w2x2_a1b2);
+SPARQ_DECLARE_TILE(launch_tile_128x256_w1x4_a2b3);
+SPARQ_DECLARE_TILE(launch_tile_128x512_w1x4_a1b3);
+
+}  // namespace sparq
