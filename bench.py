@@ -33,7 +33,8 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg3",
-                    help="cfg0 | cfg1 | cfg2 | cfg3 (default) | cfg4 | cfg4-2bit")
+                    help="cfg3 (default: explicit GEMM A[M,K]) | cfg3-conv (same M,K,N as a 3x3x512 conv) | "
+                         "cfg0 | cfg1 | cfg2 | cfg4 | cfg4-2bit")
     ap.add_argument("--mask", type=lambda s: int(s, 0), default=None, help="cfg3 only: shift mask override")
     ap.add_argument("--round", type=int, default=None, help="cfg3 only: rounding override")
     ap.add_argument("--pair", type=int, default=None, help="cfg3 only: pairing override")
@@ -49,8 +50,12 @@ def build_workload(args):
     import sparq_synth as S
     from dataclasses import replace
     wl = args.workload
-    if wl == "cfg3":
+    if wl in ("cfg3", "cfg3-conv"):
         layer = S.config3_layer(args.rows)
+        if wl == "cfg3-conv":
+            # the same GEMM seen as a convolution: 3x3, 512 -> 512 channels, 32x32 pixels, pad 1
+            layer = replace(layer, name="conv3x3_512_512_32x32", B=args.rows // 1024, H=32, W=32, C=512, KH=3, KW=3,
+                            pad=(1, 1))
         mode = layer.mode
         if args.mask is not None:
             mode = replace(mode, shift_mask=args.mask)
@@ -59,7 +64,8 @@ def build_workload(args):
         if args.pair is not None:
             mode = replace(mode, pair=args.pair)
         layer = replace(layer, mode=mode, zf=args.zf if args.zf is not None else layer.zf)
-        name = f"config3: GEMM M={layer.M} K={layer.K} N={layer.N}, {mode.label}, zf={layer.zf}"
+        form = "explicit A[M,K]" if wl == "cfg3" else f"implicit 3x3 conv B={layer.B} 32x32x512"
+        name = f"config3: GEMM M={layer.M} K={layer.K} N={layer.N} ({form}), {mode.label}, zf={layer.zf}"
         return 3, [layer], name
     if wl == "cfg0":
         return 0, S.config0(), "config0: 3x3 conv 56x56x64->64, batch 1"
@@ -205,8 +211,16 @@ def main():
             xh, wh, sch = dom["host"]
         else:
             xh, wh, sch = S.gen_layer(cfg_id, L)
-        target_macs = 4e10 * max(1, threads) / 8          # roughly 10-30 s of oracle work
-        n_rows = int(max(16, min(L.M, target_macs / (L.K * L.N))))
+        # pilot on a few rows, then a sample sized for roughly 15 s of oracle work
+        pilot = np.linspace(0, L.M - 1, min(L.M, 64)).astype(np.int64)
+        t0 = time.perf_counter()
+        oracle.conv_gemm(xh, wh, L.stride, L.pad, scale=sch, rows=pilot, **L.mode.kwargs())
+        t_pilot = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        oracle.conv_gemm(xh, wh, L.stride, L.pad, scale=sch, rows=pilot[:1], **L.mode.kwargs())
+        t_fixed = time.perf_counter() - t0                       # trimming the whole input dominates this
+        per_row = max(1e-7, (t_pilot - t_fixed) / max(1, len(pilot) - 1))
+        n_rows = int(max(64, min(L.M, (15.0 - t_fixed) / per_row)))
         rows = np.linspace(0, L.M - 1, n_rows).astype(np.int64)
         t0 = time.perf_counter()
         oracle.conv_gemm(xh, wh, L.stride, L.pad, scale=sch, rows=rows, **L.mode.kwargs())
