@@ -37,14 +37,16 @@ inline bool mode_valid(const sparq_mode* m) {
 enum TrimKind : int {
     kTrimNone = 0,
     kTrimFloor, kTrimFloorPair, kTrimFloorPairWide,
-    kTrimRound, kTrimRoundPair, kTrimRoundPairWide,
+    kTrimRound, kTrimRoundPairWide,        // 2- and 3-bit windows
+    kTrimRound4, kTrimRoundPair4,          // 4-bit windows: cheaper saturation test
     kTrimKinds
 };
 
 inline TrimKind trim_kind(const sparq_mode* m) {
     if (m->window_bits == 8) return kTrimNone;
     const bool wide = m->pair && m->window_bits < 4;
-    if (m->round_nearest) return !m->pair ? kTrimRound : (wide ? kTrimRoundPairWide : kTrimRoundPair);
+    if (m->round_nearest && m->window_bits == 4) return m->pair ? kTrimRoundPair4 : kTrimRound4;
+    if (m->round_nearest) return wide ? kTrimRoundPairWide : kTrimRound;
     return !m->pair ? kTrimFloor : (wide ? kTrimFloorPairWide : kTrimFloorPair);
 }
 
@@ -55,7 +57,8 @@ __device__ __forceinline__ uint32_t trim4_kind(uint32_t x, const TrimLuts& L) {
     else if constexpr (KIND == kTrimFloorPair) return trim4<false, true, false>(x, L);
     else if constexpr (KIND == kTrimFloorPairWide) return trim4<false, true, true>(x, L);
     else if constexpr (KIND == kTrimRound) return trim4<true, false, false>(x, L);
-    else if constexpr (KIND == kTrimRoundPair) return trim4<true, true, false>(x, L);
+    else if constexpr (KIND == kTrimRound4) return trim4_round_n4<false>(x, L);
+    else if constexpr (KIND == kTrimRoundPair4) return trim4_round_n4<true>(x, L);
     else return trim4<true, true, true>(x, L);
 }
 

@@ -50,8 +50,9 @@ constexpr int lcm3(int a, int b, int c) { int l = a / gcd2(a, b) * b; return l /
 // Tile shape: TM output pixels x TN output channels per workgroup, WGM x WGN
 // wavefronts.  PA / PB: how many reduction steps ahead of their consumption the
 // activation / weight loads are issued.
-template <int TM, int TN, int WGM, int WGN, int PA, int PB>
+template <int TM, int TN, int WGM, int WGN, int PA, int PB, bool SPLIT = false>
 struct TileCfg {
+    static constexpr bool kSplitTrim = SPLIT;                   // trim half of the activations in each scheduling region
     static constexpr int kTM = TM, kTN = TN, kWGM = WGM, kWGN = WGN, kPA = PA, kPB = PB;
     static constexpr int kThreads = 64 * WGM * WGN;
     static constexpr int kWTM = TM / WGM, kWTN = TN / WGN;      // per-wavefront tile
@@ -146,11 +147,11 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
             ++a_step;
         };
 
-        // trim + flip to signed + stage in LDS
-        auto store_a = [&](int stage, const v4u (&ar)[AC]) {
+        // trim + flip to signed + stage in LDS; chunks [i0, i1) of this lane
+        auto store_a = [&](int stage, const v4u (&ar)[AC], int i0, int i1) {
             uint8_t* sa = lds + stage * Cfg::kLdsA + kc * Cfg::kPlaneA + (tid >> 2) * kChunk;
 #pragma unroll
-            for (int i = 0; i < AC; ++i) {
+            for (int i = i0; i < i1; ++i) {
                 v4u v = ar[i];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) v[j] = trim4_kind<KIND>(v[j], p.luts) ^ 0x80808080u;
@@ -209,8 +210,8 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
                 load_b(b_reg[u][1], 1);
                 advance_b();
             }
-            store_a(0, a0);
-            store_a(1, a1);
+            store_a(0, a0, 0, AC);
+            store_a(1, a1, 0, AC);
         }
         __syncthreads();
         load_frags(0, a_frag[0]);
@@ -237,8 +238,10 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
                 for (int j = 0; j < FN; ++j)
                     c[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur[0][i], br[0][j], c[i][j], 0, 0, 0);
             load_b(br[0], 0);
+            constexpr int kFirst = Cfg::kSplitTrim ? AC / 2 : 0;
+            store_a(st2, a_old, 0, kFirst);
             __builtin_amdgcn_sched_barrier(0);
-            store_a(st2, a_old);
+            store_a(st2, a_old, kFirst, AC);
 #pragma unroll
             for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -330,7 +333,8 @@ sparq_status launch_kind(TrimKind kind, const GemmParams& p, hipStream_t s) {
         case kTrimFloorPair: return launch_cfg<Cfg, kTrimFloorPair>(p, s);
         case kTrimFloorPairWide: return launch_cfg<Cfg, kTrimFloorPairWide>(p, s);
         case kTrimRound: return launch_cfg<Cfg, kTrimRound>(p, s);
-        case kTrimRoundPair: return launch_cfg<Cfg, kTrimRoundPair>(p, s);
+        case kTrimRound4: return launch_cfg<Cfg, kTrimRound4>(p, s);
+        case kTrimRoundPair4: return launch_cfg<Cfg, kTrimRoundPair4>(p, s);
         default: return launch_cfg<Cfg, kTrimRoundPairWide>(p, s);
     }
 }

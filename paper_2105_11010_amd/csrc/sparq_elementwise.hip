@@ -113,7 +113,8 @@ static void launch_trim_pad_kind(const uint8_t* x, uint8_t* xp, int64_t pixels, 
         case kTrimFloorPair: FN<kTrimFloorPair>(__VA_ARGS__); break;                        \
         case kTrimFloorPairWide: FN<kTrimFloorPairWide>(__VA_ARGS__); break;                \
         case kTrimRound: FN<kTrimRound>(__VA_ARGS__); break;                                \
-        case kTrimRoundPair: FN<kTrimRoundPair>(__VA_ARGS__); break;                        \
+        case kTrimRound4: FN<kTrimRound4>(__VA_ARGS__); break;                              \
+        case kTrimRoundPair4: FN<kTrimRoundPair4>(__VA_ARGS__); break;                      \
         default: FN<kTrimRoundPairWide>(__VA_ARGS__); break;                                \
     }
 

@@ -41,6 +41,7 @@ struct TrimLuts {
     uint32_t b_lo, b_hi;     //                low mask by (x >> 2) & 7
     uint32_t wa_lo, wa_hi;   // 2n-bit window (zero partner, n < 4): same two tables
     uint32_t wb_lo, wb_hi;
+    uint32_t ncap_lo, ncap_hi; // n = 4 rounding: 256 - (first value that saturates), by (x >> 5); 0 = never
     uint32_t ones_n;         // 2^n  - 1 in every byte
     uint32_t ones_w;         // 2^2n - 1 in every byte
     uint32_t n;              // window bits
@@ -84,6 +85,19 @@ inline TrimLuts make_luts(int n, uint32_t S) {
     if (n >= 8) return L;                      // plain 8-bit layer: tables unused
     fill_tables(n, S, &L.a_lo, &L.a_hi, &L.b_lo, &L.b_hi);
     if (2 * n < 8) fill_tables(2 * n, wide_shift_mask(n, S), &L.wa_lo, &L.wa_hi, &L.wb_lo, &L.wb_hi);
+    if (n == 4) {
+        // A value saturates when its leading one sits at the window top and the window plus
+        // the rounding bit are all ones: x >= 2^(p+1) - 2^(s-1).  Index 0 stands for p = 4
+        // (smaller values never round up past 15).
+        static const int pa[8] = {4, 5, 6, 6, 7, 7, 7, 7};
+        uint64_t C = 0;
+        for (int i = 0; i < 8; ++i) {
+            const int p = pa[i], sh = trim_shift_for(p, 4, S);
+            const uint64_t ncap = (sh >= 1 && p == sh + 3) ? 256u - (1u << (p + 1)) + (1u << (sh - 1)) : 0u;
+            C |= (ncap & 0xFF) << (8 * i);
+        }
+        L.ncap_lo = (uint32_t)C; L.ncap_hi = (uint32_t)(C >> 32);
+    }
     L.ones_n = 0x01010101u * ((1u << n) - 1u);
     L.ones_w = 0x01010101u * ((1u << (2 * n > 8 ? 8 : 2 * n)) - 1u);
     return L;
@@ -166,10 +180,25 @@ SPARQ_HD uint32_t trim4(uint32_t x, const TrimLuts& L) {
     return fl + (r << 1);
 }
 
+// n = 4 with rounding: the saturation test is a byte-wise compare against a per-region
+// threshold (one table lookup + v_lerp_u8), and rounding is "add the half bit, then drop the
+// residual": x + 2^(s-1) cannot leave the byte unless the value saturates.
+template <bool PAIR>
+SPARQ_HD uint32_t trim4_round_n4(uint32_t x, const TrimLuts& L) {
+    const uint32_t selA = (x >> 5) & 0x07070707u;
+    const uint32_t selB = (x >> 2) & 0x07070707u;
+    uint32_t low = low_mask(selA, selB, L.a_hi, L.a_lo, L.b_hi, L.b_lo);
+    if (PAIR) low &= expand_bit7_swapped(nonzero_flag(x));
+    const uint32_t half = low & ~(low >> 1);
+    const uint32_t sat = expand_bit7(lerp(x, perm(L.ncap_hi, L.ncap_lo, selA), 0u));   // x + (256 - cap) >= 256
+    return (x + (half & ~sat)) & ~low;
+}
+
 // Runtime-dispatched form for code that is not performance critical.
 SPARQ_HD uint32_t trim4_any(uint32_t x, const TrimLuts& L, bool round_nearest, bool pair) {
     if (L.n >= 8) return x;
     const bool wide = pair && L.n < 4;
+    if (round_nearest && L.n == 4) return pair ? trim4_round_n4<true>(x, L) : trim4_round_n4<false>(x, L);
     if (round_nearest) {
         if (!pair) return trim4<true, false, false>(x, L);
         return wide ? trim4<true, true, true>(x, L) : trim4<true, true, false>(x, L);
