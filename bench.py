@@ -30,11 +30,11 @@ PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E, published
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="cfg3",
                     help="cfg3 (default: explicit GEMM A[M,K]) | cfg3-conv (same M,K,N as a 3x3x512 conv) | "
-                         "cfg0 | cfg1 | cfg2 | cfg4 | cfg4-2bit")
+                         "cfg0 | cfg1 | cfg2 | cfg4 | cfg4-2bit | cfg3-sweep (all 36 option points, table on stderr)")
     ap.add_argument("--mask", type=lambda s: int(s, 0), default=None, help="cfg3 only: shift mask override")
     ap.add_argument("--round", type=int, default=None, help="cfg3 only: rounding override")
     ap.add_argument("--pair", type=int, default=None, help="cfg3 only: pairing override")
@@ -43,6 +43,7 @@ def parse_args():
     ap.add_argument("--batch", type=int, default=None, help="cfg1/2/4: batch override")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-layer", action="store_true", help="print a per-layer table on stderr")
+    ap.add_argument("--no-extra", action="store_true", help="skip the secondary ResNet-18 figure of the default run")
     return ap.parse_args()
 
 
@@ -79,7 +80,98 @@ def build_workload(args):
         b = args.batch or 128
         mode = S.Mode(2, S.OPT7_2B, 1, 1) if wl.endswith("2bit") else None
         return 4, S.config4(b, mode), f"config4: Inception-v3-shaped convs, batch {b}" + (", 2-bit 7opt" if mode else "")
+    if wl == "cfg3-sweep":
+        return 3, [], "config3 sweep"
     raise SystemExit(f"unknown workload {wl}")
+
+
+def prepare(sq, S, torch, dev, cfg_id, layers, keep_host=False):
+    """Generate every layer's tensors, upload them and pack the weights (all before any timing)."""
+    items = []
+    for layer in layers:
+        x, w, sc = S.gen_layer(cfg_id, layer)
+        d = sq.conv_desc(layer.B, layer.H, layer.W, layer.C, layer.N, layer.KH, layer.KW, layer.stride, layer.pad)
+        m = sq.mode(*layer.mode.astuple())
+        xd = torch.from_numpy(x).to(dev)
+        wd = torch.from_numpy(w).to(dev)
+        sd = torch.from_numpy(sc).to(dev)
+        packed = torch.empty(sq.sparq_packed_bytes(d), dtype=torch.uint8, device=dev)
+        sq.sparq_pack_weights(wd, d, packed)
+        wsb = sq.sparq_workspace_bytes(d, m)
+        ws = torch.empty(wsb, dtype=torch.uint8, device=dev) if wsb else None
+        out = torch.empty((layer.M, layer.N), dtype=torch.float32, device=dev)
+        items.append(dict(layer=layer, d=d, m=m, x=xd, sc=sd, packed=packed, ws=ws, out=out,
+                          host=(x, w, sc) if keep_host else None))
+        del wd
+    torch.cuda.synchronize()
+    return items
+
+
+def run_step(sq, items):
+    for it in items:
+        for _ in range(it["layer"].repeat):
+            sq.sparq_conv_gemm(it["x"], it["packed"], it["d"], it["m"], acc=None, scale=it["sc"], out=it["out"],
+                               workspace=it["ws"])
+
+
+def time_steps(sq, torch, items, warmup, steps):
+    """(device ms per step from HIP events on the launch stream, host wall ms per step)."""
+    for _ in range(warmup):
+        run_step(sq, items)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        run_step(sq, items)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps, (time.perf_counter() - t0) * 1e3 / steps
+
+
+def sweep(args, sq, S, torch, dev):
+    """The option sweep: {2opt,3opt,5opt} x {floor,round} x pairing {off,on} x zero fraction {.2,.5,.8}
+    on M=65536, K=4608, N=512; fused conv-GEMM TOPS and standalone trim GB/s for each point."""
+    from dataclasses import replace
+    points, by_zf = [], {}
+    for mode, zf in S.config3_sweep():
+        by_zf.setdefault(zf, []).append(mode)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    print(f"{'mode':24s} {'zf':>4s} {'gemm ms':>9s} {'TOPS':>8s} {'trim GB/s':>10s}", file=sys.stderr)
+    tot_ops = tot_ms = 0.0
+    for zf, modes in by_zf.items():
+        base = replace(S.config3_layer(args.rows), zf=zf)
+        items = prepare(sq, S, torch, dev, 3, [base])
+        it = items[0]
+        y = torch.empty_like(it["x"])
+        for mode in modes:
+            it["layer"] = replace(base, mode=mode)
+            it["m"] = sq.mode(*mode.astuple())
+            ms, _ = time_steps(sq, torch, items, max(5, args.warmup // 5), max(10, args.steps // 10))
+            for _ in range(2):
+                sq.sparq_trim(it["x"], y, it["m"])
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(10):
+                sq.sparq_trim(it["x"], y, it["m"])
+            e1.record()
+            torch.cuda.synchronize()
+            gbps = 2 * y.numel() / (e0.elapsed_time(e1) / 10 * 1e-3) / 1e9
+            t = base.ops / ms / 1e9
+            tot_ops += base.ops
+            tot_ms += ms
+            points.append({"mode": mode.label, "zf": zf, "ms": round(ms, 4), "TOPS": round(t, 1), "trim_GBps": round(gbps, 1)})
+            print(f"{mode.label:24s} {zf:4.1f} {ms:9.4f} {t:8.1f} {gbps:10.1f}", file=sys.stderr, flush=True)
+        del items, it, y
+        torch.cuda.empty_cache()
+    tops = tot_ops / (tot_ms * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "SPARQ conv-GEMM TOPS (int8-equiv)", "value": round(tops, 2), "unit": "TOPS", "n_gpus": 1,
+        "steps": max(10, args.steps // 10), "warmup": max(5, args.warmup // 5), "ms_per_step": round(tot_ms / len(points), 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": f"config3 sweep: {len(points)} option points on GEMM M={args.rows} K=4608 N=512 "
+                               "(value = total ops / total time over the points)"},
+        "points": points, "roofline": None, "cpu_baseline": None}), flush=True)
 
 
 def main():
@@ -99,47 +191,18 @@ def main():
     dev = torch.device("cuda:0")
     cfg_id, layers, wl_name = build_workload(args)
 
+    if args.workload == "cfg3-sweep":
+        return sweep(args, sq, S, torch, dev)
+
     # ---- inputs resident in HBM before anything is timed ----
     t_gen = time.time()
-    items = []
-    for layer in layers:
-        x, w, sc = S.gen_layer(cfg_id, layer)
-        d = sq.conv_desc(layer.B, layer.H, layer.W, layer.C, layer.N, layer.KH, layer.KW, layer.stride, layer.pad)
-        m = sq.mode(*layer.mode.astuple())
-        xd = torch.from_numpy(x).to(dev)
-        wd = torch.from_numpy(w).to(dev)
-        sd = torch.from_numpy(sc).to(dev)
-        packed = torch.empty(sq.sparq_packed_bytes(d), dtype=torch.uint8, device=dev)
-        sq.sparq_pack_weights(wd, d, packed)
-        wsb = sq.sparq_workspace_bytes(d, m)
-        ws = torch.empty(wsb, dtype=torch.uint8, device=dev) if wsb else None
-        out = torch.empty((layer.M, layer.N), dtype=torch.float32, device=dev)
-        items.append(dict(layer=layer, d=d, m=m, x=xd, sc=sd, packed=packed, ws=ws, out=out,
-                          host=(x, w, sc) if len(layers) == 1 else None))
-        del wd
-    torch.cuda.synchronize()
+    items = prepare(sq, S, torch, dev, cfg_id, layers, keep_host=len(layers) == 1)
     print(f"[bench] inputs generated and uploaded in {time.time() - t_gen:.1f}s", file=sys.stderr, flush=True)
 
-    def step():
-        for it in items:
-            for _ in range(it["layer"].repeat):
-                sq.sparq_conv_gemm(it["x"], it["packed"], it["d"], it["m"], acc=None, scale=it["sc"], out=it["out"],
-                                   workspace=it["ws"])
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    e0.record()
-    for _ in range(args.steps):
-        step()
-    e1.record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    ms_per_step = e0.elapsed_time(e1) / args.steps
+    ms_per_step, wall_ms = time_steps(sq, torch, items, args.warmup, args.steps)
     total_ops = S.total_ops(layers)
     tops = total_ops / (ms_per_step * 1e-3) / 1e12
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
 
     # ---- dominant kernel: the fused conv-GEMM of the largest layer, timed on its own ----
     dom = max(items, key=lambda it: it["layer"].ops * it["layer"].repeat)
@@ -201,6 +264,21 @@ def main():
             print(f"{L.name:28s} {L.M:8d} {L.K:6d} {L.N:5d} {L.repeat:3d} {ms:9.4f} {L.ops / ms / 1e9:8.1f}",
                   file=sys.stderr)
 
+    # ---- secondary figures of the default run: the same GEMM as an implicit 3x3 convolution, and the
+    #      ResNet-18 layer table (small layers that do not fill the chip) ----
+    also = None
+    if args.workload == "cfg3" and not args.no_extra and args.rows == 65536:
+        also = []
+        for wl in ("cfg3-conv", "cfg1"):
+            a2 = argparse.Namespace(**{**vars(args), "workload": wl})
+            c2, l2, n2 = build_workload(a2)
+            it2 = prepare(sq, S, torch, dev, c2, l2)
+            ms2, _ = time_steps(sq, torch, it2, args.warmup, args.steps)
+            also.append({"workload": n2, "value": round(S.total_ops(l2) / ms2 / 1e9, 2), "unit": "TOPS",
+                         "ms_per_step": round(ms2, 4), "total_gop": round(S.total_ops(l2) / 1e9, 3)})
+            del it2
+            torch.cuda.empty_cache()
+
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload ----
     cpu = None
     if not args.no_cpu_baseline:
@@ -253,6 +331,8 @@ def main():
                     "ms": round(deq_ms, 4)},
         "cpu_baseline": cpu,
     }
+    if also:
+        line["also"] = also
     print(json.dumps(line), flush=True)
 
 

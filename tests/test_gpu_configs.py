@@ -1,0 +1,119 @@
+"""GPU parity at the benchmark's full sizes: every layer of the five workload tables runs through
+the C ABI exactly as bench.py launches it (full tensors, fused dequantisation); the CPU oracle then
+recomputes a sample of output rows one by one -- first and last tile, image borders, random interior
+rows -- and those must match bit-exactly (int32) and to 1e-6 relative (fp32)."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+import sparq_synth as S
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def sq():
+    assert torch.cuda.is_available(), "GPU tests need a device"
+    import paper_2105_11010_amd as sq_
+    return sq_
+
+
+def sample_rows(layer, n=160, seed=0):
+    """Output rows to recompute: tile edges, image borders, and a random remainder."""
+    M, Ho, Wo = layer.M, layer.Ho, layer.Wo
+    rows = {0, 1, 127, 128, 129, M - 1, M - 2, M - 128, M - 129, M // 2}
+    for b in (0, layer.B - 1):
+        base = b * Ho * Wo
+        for oy in (0, Ho - 1, Ho // 2):
+            for ox in (0, Wo - 1, Wo // 3):
+                rows.add(base + oy * Wo + ox)
+    rng = np.random.default_rng(1234 + seed)
+    rows.update(int(r) for r in rng.integers(0, M, size=n))
+    return np.array(sorted(r for r in rows if 0 <= r < M), dtype=np.int64)
+
+
+def check_sampled(sq, oracle, cfg_id, layer, n=160, modes=None):
+    """Run `layer` at full size under each mode (default: the layer's own) on one set of tensors."""
+    data = S.gen_layer(cfg_id, layer)
+    for mode in modes or [layer.mode]:
+        _check_one(sq, oracle, replace(layer, mode=mode), data, n)
+
+
+def _check_one(sq, oracle, layer, data, n):
+    x, w, sc = data
+    d = sq.conv_desc(layer.B, layer.H, layer.W, layer.C, layer.N, layer.KH, layer.KW, layer.stride, layer.pad)
+    m = sq.mode(*layer.mode.astuple())
+    dev = torch.device("cuda:0")
+    xd, wd, sd = (torch.from_numpy(a).to(dev) for a in (x, w, sc))
+    packed = torch.empty(sq.sparq_packed_bytes(d), dtype=torch.uint8, device=dev)
+    sq.sparq_pack_weights(wd, d, packed)
+    wsb = sq.sparq_workspace_bytes(d, m)
+    ws = torch.empty(wsb, dtype=torch.uint8, device=dev) if wsb else None
+    acc = torch.empty((layer.M, layer.N), dtype=torch.int32, device=dev)
+    out = torch.empty((layer.M, layer.N), dtype=torch.float32, device=dev)
+    sq.sparq_conv_gemm(xd, packed, d, m, acc=acc, scale=sd, out=out, workspace=ws)
+    rows = sample_rows(layer, n, seed=layer.index)
+    ridx = torch.from_numpy(rows).to(dev)
+    got_acc = acc[ridx].cpu().numpy()
+    got_out = out[ridx].cpu().numpy()
+    # a property that holds at any size: the fused fp32 output is the dequantised accumulator
+    deq = torch.empty_like(out)
+    sq.sparq_dequant(acc, sd, deq)
+    assert torch.equal(deq, out), f"{layer.name}: fused and standalone dequantisation differ"
+    torch.cuda.synchronize()
+    del acc, out, deq, xd
+    ref_acc, ref_out = oracle.conv_gemm(x, w, layer.stride, layer.pad, scale=sc, rows=rows, **layer.mode.kwargs())
+    assert np.array_equal(got_acc, ref_acc), f"{layer.name} {layer.mode.label}: int32 mismatch on sampled rows"
+    assert np.all(np.abs(got_out.astype(np.float64) - ref_out) <= 1e-6 * np.abs(ref_out)), f"{layer.name}: fp32 off"
+
+
+# ---- config 1: ResNet-18, batch 32, 3opt floor (first conv plain 8-bit) --------------------------
+@pytest.mark.parametrize("layer", S.config1(), ids=lambda l: l.name)
+def test_config1_resnet18(sq, oracle, layer):
+    check_sampled(sq, oracle, 1, layer)
+
+
+# ---- config 2: ResNet-50, batch 256, 5opt round ---------------------------------------------------
+_C2 = S.config2()
+_C2_FULL = {"conv1_7x7s2", "s1b1_1x1_64_256", "s1bx_1x1_256_64", "s2b1_3x3s2_128", "s2proj_1x1s2_256_512",
+            "s3bx_3x3_256", "s4bx_3x3_512", "s4bx_1x1_512_2048"}
+
+
+@pytest.mark.parametrize("layer", [l for l in _C2 if l.name in _C2_FULL], ids=lambda l: l.name)
+def test_config2_resnet50_full_batch(sq, oracle, layer):
+    """The largest tensors of the stack at batch 256 (input up to 205 MB, fp32 output up to 822 MB)."""
+    check_sampled(sq, oracle, 2, layer, n=96)
+
+
+@pytest.mark.parametrize("layer", [replace(l, B=8) for l in _C2 if l.name not in _C2_FULL], ids=lambda l: l.name)
+def test_config2_resnet50_other_layers_small_batch(sq, oracle, layer):
+    check_sampled(sq, oracle, 2, layer, n=96)
+
+
+# ---- config 3: the option sweep on M=65536, K=4608, N=512 ------------------------------------------
+@pytest.mark.parametrize("zf,modes", [(0.5, [S.Mode(4, S.OPT5, 1, 1), S.Mode(4, S.OPT5, 0, 0)]),
+                                      (0.2, [S.Mode(4, S.OPT3, 0, 1)]),
+                                      (0.8, [S.Mode(4, S.OPT2, 1, 0)])], ids=["zf0.5", "zf0.2", "zf0.8"])
+def test_config3_full_size(sq, oracle, zf, modes):
+    check_sampled(sq, oracle, 3, replace(S.config3_layer(), zf=zf), n=64, modes=modes)
+
+
+def test_config3_full_size_as_convolution(sq, oracle):
+    """The same M, K, N as a 3x3 convolution over 512 channels (the form bench.py also times)."""
+    layer = replace(S.config3_layer(), name="conv3x3_512_512_32x32", B=64, H=32, W=32, C=512, KH=3, KW=3, pad=(1, 1))
+    check_sampled(sq, oracle, 3, layer, n=64)
+
+
+@pytest.mark.parametrize("mode,zf", S.config3_sweep(), ids=lambda v: v.label if isinstance(v, S.Mode) else f"zf{v}")
+def test_config3_sweep_all_36_points_small_m(sq, oracle, mode, zf):
+    check_sampled(sq, oracle, 3, replace(S.config3_layer(1024 + 77), mode=mode, zf=zf), n=48)
+
+
+# ---- config 4: Inception-v3-shaped layers, batch 128, 4-bit 5opt and 2-bit 7opt ---------------------
+@pytest.mark.parametrize("layer", S.config4(), ids=lambda l: l.name)
+def test_config4_inception_4bit_and_2bit(sq, oracle, layer):
+    """Both passes of the workload on the same tensors: 4-bit 5opt rounding, then the 2-bit window
+    with 7 shifts where a zero partner grants 4 bits."""
+    check_sampled(sq, oracle, 4, layer, n=96, modes=[layer.mode, S.Mode(2, S.OPT7_2B, 1, 1)])
