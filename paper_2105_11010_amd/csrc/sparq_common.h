@@ -67,9 +67,10 @@ struct ConvGeom {
     int B, H, W, C, N, KH, KW, sh, sw, ph, pw;
     int Ho, Wo;
     int64_t M;
-    int Cp;          // channels padded to a multiple of 16 (what the kernel sees)
+    int Cp;          // channels padded to a multiple of 16 (what the kernel loads)
+    int Cq;          // one filter tap's extent in the packed weights: C padded to 64 (to 16 when C <= 32)
     int K;           // KH*KW*C   (the method's dot-product length)
-    int Kk;          // KH*KW*Cp  (what the kernel contracts over)
+    int Kk;          // KH*KW*Cq  (what the kernel contracts over; with C > 32 every 64-byte step lies inside one tap)
     int Kp;          // Kk padded to kStepK
     int Np;          // N padded to kPadN
     size_t w_off;    // byte offset of the weight tiles inside the packed buffer
@@ -93,7 +94,8 @@ inline bool conv_geom(const sparq_conv_desc* d, ConvGeom* g) {
     if (K * 255 * 127 > 2147483647LL) return false;
     g->K = (int)K;
     g->Cp = (int)round_up(d->C, kChunk);
-    const int64_t Kk = (int64_t)d->KH * d->KW * g->Cp;
+    g->Cq = d->C > 32 ? (int)round_up(d->C, kStepK) : g->Cp;     // few channels: taps stay densely packed
+    const int64_t Kk = (int64_t)d->KH * d->KW * g->Cq;
     if (Kk > (1 << 24)) return false;
     g->Kk = (int)Kk;
     g->Kp = (int)round_up(Kk, kStepK);
@@ -107,6 +109,18 @@ inline bool conv_geom(const sparq_conv_desc* d, ConvGeom* g) {
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 inline sparq_status launch_status() { return hipGetLastError() == hipSuccess ? SPARQ_OK : SPARQ_ELAUNCH; }
+
+// Number of compute units of the current device (queried once).
+inline int device_cu_count() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 256;
+        cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    }
+    return cus;
+}
 
 // Implemented in sparq_elementwise.hip: trimmed copy of x with channels padded to Cp.
 sparq_status launch_trim_pad(const uint8_t* x, uint8_t* xp, int64_t pixels, int C, int Cp,

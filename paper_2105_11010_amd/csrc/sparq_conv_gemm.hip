@@ -1,13 +1,14 @@
 // Host entry point of the fused SPARQ convolution: validation, the channel-padding
 // pre-pass for channel counts that are not a multiple of 16, and the choice of tile shape.
 #include "sparq_conv_gemm_kernel.h"
-
-#include <string.h>
-
-
-using namespace sparq;
+#include "sparq_conv_patch_kernel.h"
 
 #include <stdlib.h>
+#include <string.h>
+
+#include <mutex>
+
+using namespace sparq;
 
 namespace {
 
@@ -21,13 +22,122 @@ const TileEntry kTiles[] = {
 // Tile choice: the widest output-channel tile the layer fills, so that an activation
 // is gathered and trimmed as few times as possible.  SPARQ_TILE=<name> (a tuning knob,
 // not part of the interface) forces one.
+// A tile shape is usable only if all its weight loads stay inside the padded buffer.
+bool tile_fits(int tn, const ConvGeom& g) { return round_up(g.N, tn) <= g.Np; }
+
 TileLauncher pick_tile(const ConvGeom& g) {
     if (const char* e = getenv("SPARQ_TILE"))
         for (const TileEntry& t : kTiles)
-            if (!strcmp(e, t.name) && t.tn <= g.Np) return t.fn;   // weight loads must stay inside the padded buffer
-    if (g.N > 256) return kTiles[2].fn;
+            if (!strcmp(e, t.name) && tile_fits(t.tn, g)) return t.fn;
+    if (g.N > 256 && tile_fits(512, g)) return kTiles[2].fn;
     if (g.N > 128) return kTiles[1].fn;
     return kTiles[0].fn;
+}
+
+// ---- input-patch kernel: eligibility and variant choice --------------------------------------
+struct PatchVariant { int tn, ac, cbs; PatchLauncher fn; };
+const PatchVariant kPatchVariants[] = {
+    {64, 2, 1, launch_patch_n64_a2c1},   {64, 4, 1, launch_patch_n64_a4c1},   {64, 8, 1, launch_patch_n64_a8c1},
+    {64, 4, 2, launch_patch_n64_a4c2},   {64, 8, 4, launch_patch_n64_a8c4},
+    {128, 2, 1, launch_patch_n128_a2c1}, {128, 4, 1, launch_patch_n128_a4c1}, {128, 8, 1, launch_patch_n128_a8c1},
+    {128, 4, 2, launch_patch_n128_a4c2}, {128, 8, 4, launch_patch_n128_a8c4},
+    {256, 2, 1, launch_patch_n256_a2c1}, {256, 4, 1, launch_patch_n256_a4c1}, {256, 8, 1, launch_patch_n256_a8c1},
+    {256, 4, 2, launch_patch_n256_a4c2}, {256, 8, 4, launch_patch_n256_a8c4},
+};
+
+// Largest patch (in pixels) any tile of this geometry needs.  Tile positions repeat relative to the
+// image with period lcm(128, Ho*Wo), so one period plus the last tile is an exact walk; results
+// are cached because the same layers are launched over and over.
+int patch_npix_max(const PatchGeom& g) {
+    struct Key { int v[12]; int npix; };
+    static Key cache[64];
+    static int used = 0, next = 0;
+    static std::mutex mu;
+    const int key[12] = {g.M, g.B, g.H, g.W, g.KH, g.KW, g.sh, g.sw, g.ph, g.pw, g.Ho, g.Wo};
+    std::lock_guard<std::mutex> lock(mu);
+    for (int i = 0; i < used; ++i)
+        if (!memcmp(cache[i].v, key, sizeof(key))) return cache[i].npix;
+    const int64_t img = (int64_t)g.Ho * g.Wo;
+    int64_t a = kPatchTM, b = img;
+    while (b) { const int64_t t = a % b; a = b; b = t; }
+    const int64_t period_tiles = img / a;                       // lcm(TM, img) / TM
+    const int64_t tiles = ((int64_t)g.M + kPatchTM - 1) / kPatchTM;
+    int npix = 0;
+    for (int64_t t = 0; t < tiles && t <= period_tiles; ++t) {
+        const int n = tile_patch(g, (int)(t * kPatchTM)).npix;
+        npix = n > npix ? n : npix;
+    }
+    const int n_last = tile_patch(g, (int)((tiles - 1) * kPatchTM)).npix;
+    npix = n_last > npix ? n_last : npix;
+    Key& slot = cache[used < 64 ? used++ : (next++ & 63)];
+    memcpy(slot.v, key, sizeof(key));
+    slot.npix = npix;
+    return npix;
+}
+
+// Fills `pg`, `npix`, and picks staging (chunks per lane, channel block); false: not eligible.
+bool plan_patch(const ConvGeom& g, PatchGeom* pg, int* npix, int* ac, int* cbs) {
+    if (g.Cq % kStepK != 0) return false;                        // fewer than 33 channels: taps are not step-aligned
+    if (g.M >= kPatchMaxDividend || (size_t)g.Kp * g.Np >= kPatchInvalidOffset) return false;
+    PatchGeom q{};
+    const bool gemm = g.KH == 1 && g.KW == 1 && g.sh == 1 && g.sw == 1 && g.ph == 0 && g.pw == 0;
+    if (gemm) {                                                  // 1x1, stride 1: one long row of pixels
+        q.B = 1; q.H = 1; q.W = (int)g.M; q.Ho = 1; q.Wo = (int)g.M; q.KH = q.KW = 1; q.sh = q.sw = 1;
+    } else {
+        q.B = g.B; q.H = g.H; q.W = g.W; q.Ho = g.Ho; q.Wo = g.Wo; q.KH = g.KH; q.KW = g.KW;
+        q.sh = g.sh; q.sw = g.sw; q.ph = g.ph; q.pw = g.pw;
+    }
+    q.M = (int)g.M;
+    q.Hv = q.H + 2 * q.ph;
+    if ((int64_t)q.B * q.Hv + q.KH >= kPatchMaxDividend) return false;
+    q.rcp_wo = 1.0f / (float)q.Wo; q.rcp_ho = 1.0f / (float)q.Ho; q.rcp_hv = 1.0f / (float)q.Hv;
+    if (patch_npix_bound(q) > 4096) return false;               // far too large: skip the exact walk
+    const int n = patch_npix_max(q);
+    const int taps = q.KH * q.KW;
+    const int ksteps = g.Cq / kStepK;
+    // candidates (chunks per lane, channel block / 64): larger channel blocks first for 1x1 layers,
+    // the smallest staging that holds the patch otherwise
+    static const int cand[5][2] = {{8, 4}, {4, 2}, {2, 1}, {4, 1}, {8, 1}};
+    for (const auto& c : cand) {
+        const int a = c[0], cb = c[1];
+        if (ksteps % cb) continue;
+        if (n * 4 * cb > a * 256) continue;                      // patch does not fit the staging registers
+        if (cb > 1 && taps > 1) continue;                        // multi-tap layers: 64-channel units
+        const int as = a / 2, steps = taps * cb;
+        const int unrolled = as + (((as ^ steps) & 1) ? 1 : 0);  // as the kernel lays out a unit
+        if (cb == 1 && !(taps & 1)) continue;                    // 64-channel units need an odd tap count
+        if (steps < unrolled) continue;                          // unit too short to stage all chunks
+        *pg = q; *npix = n; *ac = a; *cbs = cb;
+        return true;
+    }
+    return false;
+}
+
+// Output-channel tile of the patch kernel: 64 for narrow layers; otherwise 128 (two workgroups per
+// CU hide each other's latencies), 256 only for long reductions over a multiple of 256 channels
+// with enough tiles to fill the chip.  SPARQ_PATCH_TN=<n> (a tuning knob) forces one.
+PatchLauncher pick_patch(const ConvGeom& g, int ac, int cbs) {
+    const int64_t tiles_m = (g.M + kPatchTM - 1) / kPatchTM;
+    int tn = g.N <= 64 ? 64 : 128;
+    if (g.N >= 512 && g.N % 256 == 0 && g.K >= 2048 && tiles_m * (g.N / 256) >= device_cu_count()) tn = 256;
+    if (const char* e = getenv("SPARQ_PATCH_TN")) {
+        const int v = atoi(e);
+        if ((v == 64 || v == 128 || v == 256) && tile_fits(v, g)) tn = v;
+    }
+    for (const PatchVariant& v : kPatchVariants)
+        if (v.tn == tn && v.ac == ac && v.cbs == cbs) return v.fn;
+    return nullptr;
+}
+
+// 1x1 stride-1 layers with a long reduction have nothing to reuse between taps; when they also
+// fill the chip with wide tiles and waste little on channel padding, the gather kernel's wider
+// tiles (each activation trimmed once for up to 512 output channels) are faster.
+bool prefer_gather(const ConvGeom& g) {
+    const bool gemm = g.KH == 1 && g.KW == 1 && g.sh == 1 && g.sw == 1 && g.ph == 0 && g.pw == 0;
+    if (!gemm || g.K < 768) return false;
+    const int tn = (g.N > 256 && tile_fits(512, g)) ? 512 : g.N > 128 ? 256 : 128;
+    const int64_t tiles = (g.M + 127) / 128 * ((g.N + tn - 1) / tn);
+    return tiles >= device_cu_count() && round_up(g.N, tn) * 100 <= (int64_t)g.N * 115;
 }
 
 }  // namespace
@@ -71,6 +181,34 @@ extern "C" sparq_status sparq_conv_gemm(const uint8_t* x, const void* packed_w, 
     }
     if (x_bytes >= kInvalidOffset) return SPARQ_EUNSUPPORTED;
 
+    // Preferred: the input-patch kernel (activations loaded and trimmed once per tile and channel
+    // block).  SPARQ_PATH=gather|patch (a tuning knob, not part of the interface) forces one of the two kernels.
+    const char* path = getenv("SPARQ_PATH");
+    PatchGeom pg;
+    int npix = 0, ac = 0, cbs = 0;
+    ConvGeom gk = g;
+    gk.C = gk.Cp;                                                // what the kernel sees after the padding pre-pass
+    const bool force_gather = path && !strcmp(path, "gather"), force_patch = path && !strcmp(path, "patch");
+    if (!force_gather && (force_patch || !prefer_gather(g)) && plan_patch(gk, &pg, &npix, &ac, &cbs)) {
+        if (PatchLauncher fn = pick_patch(g, ac, cbs)) {
+            PatchParams q{};
+            q.x = xin;
+            q.wpk = static_cast<const uint8_t*>(packed_w) + g.w_off;
+            q.colsum = static_cast<const int32_t*>(packed_w);
+            q.acc = acc; q.scale = scale; q.out = out;
+            q.x_bytes = (uint32_t)x_bytes;
+            q.w_bytes = (uint32_t)((size_t)g.Kp * g.Np);
+            q.N = g.N; q.Np = g.Np; q.C = g.Cp;
+            q.ksteps_tap = g.Cq / kStepK;
+            q.ncb = q.ksteps_tap / cbs;
+            q.nsteps = g.KH * g.KW * cbs;
+            q.g = pg;
+            q.luts = make_luts(mode->window_bits, mode->shift_mask);
+            const sparq_status st = fn(kind, q, npix, s);
+            if (st != SPARQ_EUNSUPPORTED) return st;
+        }
+    }
+
     GemmParams p{};
     p.x = xin;
     p.wpk = static_cast<const uint8_t*>(packed_w) + g.w_off;
@@ -81,9 +219,9 @@ extern "C" sparq_status sparq_conv_gemm(const uint8_t* x, const void* packed_w, 
     p.M = g.M;
     p.x_bytes = (uint32_t)x_bytes;
     p.N = g.N; p.Np = g.Np; p.Kk = g.Kk; p.nkb = g.Kp / kStepK;
-    p.H = g.H; p.W = g.W; p.C = g.Cp; p.Ho = g.Ho; p.Wo = g.Wo; p.KH = g.KH; p.KW = g.KW;
+    p.H = g.H; p.W = g.W; p.C = g.Cp; p.Cq = g.Cq; p.Ho = g.Ho; p.Wo = g.Wo; p.KH = g.KH; p.KW = g.KW;
     p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw;
-    p.rcp_c = 1.0f / (float)g.Cp;
+    p.rcp_c = 1.0f / (float)g.Cq;
     p.rcp_kw = 1.0f / (float)g.KW;
     p.luts = make_luts(mode->window_bits, mode->shift_mask);
 

@@ -36,9 +36,9 @@ struct GemmParams {
     int64_t M;
     uint32_t x_bytes;
     int N, Np, Kk, nkb;
-    int H, W, C, Ho, Wo, KH, KW, sh, sw, ph, pw;
+    int H, W, C, Cq, Ho, Wo, KH, KW, sh, sw, ph, pw;   // C: channels per pixel in x; Cq: per tap in the packed weights
     int tiles_m, tiles_n;
-    float rcp_c, rcp_kw;     // 1/C and 1/KW for the branch-free reduction-index decode
+    float rcp_c, rcp_kw;     // 1/Cq and 1/KW for the branch-free reduction-index decode
     TrimLuts luts;
 };
 
@@ -50,7 +50,7 @@ constexpr int lcm3(int a, int b, int c) { int l = a / gcd2(a, b) * b; return l /
 // Tile shape: TM output pixels x TN output channels per workgroup, WGM x WGN
 // wavefronts.  PA / PB: how many reduction steps ahead of their consumption the
 // activation / weight loads are issued.
-template <int TM, int TN, int WGM, int WGN, int PA, int PB, bool SPLIT = false>
+template <int TM, int TN, int WGM, int WGN, int PA, int PB, bool SPLIT = false, int WPC = 0>
 struct TileCfg {
     static constexpr bool kSplitTrim = SPLIT;                   // trim half of the activations in each scheduling region
     static constexpr int kTM = TM, kTN = TN, kWGM = WGM, kWGN = WGN, kPA = PA, kPB = PB;
@@ -68,7 +68,8 @@ struct TileCfg {
     static constexpr int kStages = 3;                           // written two steps ahead, read one step ahead
     static constexpr int kLdsBytes = kStages * kLdsA;
     static constexpr int kUnroll = lcm3(2, PA, PB);             // main-loop unroll: every ring index compile-time
-    static constexpr int kWgPerCu = (kFM * kFN * 16 <= 64) ? 2 : 1;    // small accumulators: two workgroups per CU
+    // resident workgroups per CU the register budget is set for (0: two with small accumulators, else one)
+    static constexpr int kWgPerCu = WPC ? WPC : ((kFM * kFN * 16 <= 64) ? 2 : 1);
     static_assert(TM % (32 * WGM) == 0 && TN % (32 * WGN) == 0, "tile must split into 32x32 fragments");
     static_assert((TM * 4) % kThreads == 0, "activation loads must divide evenly");
     static_assert(PA >= 1 && PA <= 4 && PB >= 1 && PB <= 4, "prefetch depth");
@@ -128,14 +129,14 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
             // where this lane's 16 bytes sit in the (kh, kw, c) reduction index
             const int k = a_step * kStepK + kc * kChunk;
             int tap = (int)((float)k * p.rcp_c);
-            int c0 = k - tap * p.C;
-            tap += (c0 >= p.C) - (c0 < 0);
-            c0 = k - tap * p.C;
+            int c0 = k - tap * p.Cq;
+            tap += (c0 >= p.Cq) - (c0 < 0);
+            c0 = k - tap * p.Cq;
             int kh = (int)((float)tap * p.rcp_kw);
             int kw = tap - kh * p.KW;
             kh += (kw >= p.KW) - (kw < 0);
             kw = tap - kh * p.KW;
-            const bool k_ok = k < p.Kk;          // false in the zero-padded K tail and past the end
+            const bool k_ok = (k < p.Kk) & (c0 < p.C);   // false in a tap's channel padding and past the end
             const int32_t tap_off = (kh * p.W + kw) * p.C + c0;
 #pragma unroll
             for (int i = 0; i < AC; ++i) {
@@ -290,18 +291,6 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
             }
         }
     }   // tile loop
-}
-
-// Number of compute units of the current device (queried once).
-inline int device_cu_count() {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 256;
-        cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-    }
-    return cus;
 }
 
 template <class Cfg, int KIND>

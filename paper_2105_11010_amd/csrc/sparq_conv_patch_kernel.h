@@ -1,0 +1,437 @@
+// Fused SPARQ convolution for gfx950, input-patch form.
+//
+//   acc[m][n] = sum_{kh,kw,c} T(x)[b, oy*sh-ph+kh, ox*sw-pw+kw, c] * w[n][kh][kw][c]     (Eq. 1, trimmed activations)
+//
+// A workgroup owns tiles of 128 consecutive output pixels x TN output channels.  For one tile and
+// one block of CB input channels (a "unit") it stages the rectangle of input pixels the tile's
+// filter taps touch (sparq_patch_geom.h) in LDS: loaded with 128-bit reads, trimmed in registers
+// (vSPARQ pairs are bytes (2j, 2j+1) of a word, bSPARQ window per byte; sparq_swar.h), flipped to
+// signed (x - 128).  Every tap then reads its matrix-instruction operands from that patch at a
+// shifted position, so an activation is fetched and trimmed once per unit -- not once per tap as
+// an im2col gather would -- and there is one workgroup barrier per unit instead of one per
+// 64-byte reduction step.  Weights come pre-packed in fragment order straight from L2 into
+// registers, two steps ahead.  The epilogue adds 128 * sum_k w[n][k] (exact in int32) and applies
+// the per-channel scale (Section 5).
+//
+// Units of all tiles a workgroup owns form one continuous software pipeline: while unit u is
+// multiplied, the patch of unit u+1 is trimmed and written to the other LDS buffer and the loads
+// of unit u+2 are issued; the weight stream runs ahead across unit and tile boundaries as well.
+// This keeps short-reduction layers (1x1 convolutions, few channels) from draining the pipeline
+// at every tile.
+//
+// The paper puts its trimming unit in front of the multiplier array and notes that it is shared
+// and runs at a much lower rate than the multipliers (Section 5); staging the trimmed patch once
+// and reusing it for all taps and all output channels of the tile is that arrangement.
+#pragma once
+#include <type_traits>
+
+#include "sparq_common.h"
+#include "sparq_patch_geom.h"
+
+namespace sparq {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+
+struct PatchParams {
+    const uint8_t* x;        // activations, NHWC, C a multiple of 16
+    const uint8_t* wpk;      // packed weight tiles (taps padded to 64 channels)
+    const int32_t* colsum;   // sum_k w[n][k], Np entries
+    int32_t* acc;            // [M][N] or null
+    const float* scale;      // [N] or null
+    float* out;              // [M][N] or null
+    uint32_t x_bytes, w_bytes;
+    int N, Np, C;
+    int ncb;                 // channel blocks per tile
+    int ksteps_tap;          // 64-byte steps per filter tap in the packed weights
+    int nsteps;              // steps per unit = KH * KW * CBS
+    int plane_stride;        // bytes between the 16-channel planes of a patch buffer
+    int tiles_m, tiles_n;
+    PatchGeom g;
+    TrimLuts luts;
+};
+
+constexpr uint32_t kPatchInvalidOffset = 0x80000000u;   // beyond any buffer this kernel accepts (< 2 GiB)
+
+// TN output channels per workgroup, WGM x WGN wavefronts, AC 16-byte patch chunks per lane and
+// unit, CBS * 64 input channels per unit, WPC resident workgroups per CU the register budget allows.
+template <int TN, int WGM, int WGN, int AC, int CBS, int WPC>
+struct PatchCfg {
+    static constexpr int kTM = kPatchTM, kTN = TN, kWGM = WGM, kWGN = WGN, kAC = AC, kCBS = CBS, kWgPerCu = WPC;
+    static constexpr int kThreads = 64 * WGM * WGN;
+    static constexpr int kWTM = kTM / WGM, kWTN = TN / WGN;
+    static constexpr int kFM = kWTM / 32, kFN = kWTN / 32;
+    static constexpr int kPlanes = 4 * CBS;                  // 16-channel planes per patch buffer
+    static constexpr int kCB = 64 * CBS;
+    static constexpr int kAS = (AC + 1) / 2;                 // steps of a unit that also stage and load patch chunks
+    static constexpr int kMaxPix = AC * kThreads / kPlanes;  // patch pixels one unit can stage
+    // 64-channel units cover multi-tap filters with an odd number of taps (1x1 included); wider
+    // units are for 1x1 filters only, where steps per unit = CBS is even
+    static constexpr bool kOddSteps = CBS == 1;
+    static constexpr int kUnrolled = kAS + (((kAS & 1) != (kOddSteps ? 1 : 0)) ? 1 : 0);
+    static_assert(kThreads == 256, "patch staging assumes 256 lanes");
+    static_assert(kTM % (32 * WGM) == 0 && TN % (32 * WGN) == 0, "tile must split into 32x32 fragments");
+    static_assert(CBS == 1 || CBS == 2 || CBS == 4, "channel block");
+    static_assert(AC >= 2 && AC % 2 == 0, "chunks per lane");
+};
+
+// bytes between planes: a multiple of 256 plus 256 / planes, so that the lanes that write one
+// pixel's chunks (one plane each) and their neighbours (next pixel) hit different LDS banks
+inline int patch_plane_stride(int npix_max, int planes) {
+    return (int)round_up((int64_t)npix_max * kChunk, 256) + 256 / planes;
+}
+
+template <int V> using int_c = std::integral_constant<int, V>;
+
+template <class Cfg, int KIND>
+__global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu) void conv_patch_kernel(const PatchParams p) {
+    constexpr int NT = Cfg::kThreads, FM = Cfg::kFM, FN = Cfg::kFN, AC = Cfg::kAC, CBS = Cfg::kCBS, AS = Cfg::kAS;
+    constexpr int PL = Cfg::kPlanes, TN = Cfg::kTN;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];     // [2][PL][plane_stride]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave % Cfg::kWGM, wn = wave / Cfg::kWGM;
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const PatchGeom& g = p.g;
+    const int ntiles = p.tiles_m * p.tiles_n;
+    const int grid = (int)gridDim.x;
+    const int buf_bytes = PL * p.plane_stride;
+    const __amdgpu_buffer_rsrc_t xrsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.x), 0, (int)p.x_bytes, 0x00020000);
+
+    // ---- patch staging: chunk i of this lane is element e = tid + i * 256 of a unit, i.e. plane
+    //      e % PL (the same for every i) of patch pixel tid / PL + i * (256 / PL) ----
+    const int my_plane = tid % PL;
+    const int my_c = my_plane * kChunk;           // channel offset inside the unit's channel block
+    const int my_pix = tid / PL;
+    const int my_loff = my_plane * p.plane_stride + my_pix * kChunk;
+    const int dummy_off = 2 * buf_bytes;          // 16 spare bytes: where chunks outside the patch are written
+    v4u a_reg[AC];                                // requested chunks (of the unit after next)
+
+    // load cursor: the unit whose chunks are requested next; its tile's patch, uniform
+    int l_tile = (int)blockIdx.x, l_cb = 0;
+    TilePatch lt;
+    int stage_npix = 0;                           // patch size of the unit whose chunks are staged next
+    auto load_tile_patch = [&]() __attribute__((always_inline)) {
+        const bool live = l_tile < ntiles;
+        const TilePatch t = tile_patch(g, (live ? l_tile / p.tiles_n : 0) * kPatchTM);
+        lt.v0 = __builtin_amdgcn_readfirstlane(t.v0);
+        lt.xlo = __builtin_amdgcn_readfirstlane(t.xlo);
+        lt.pwt = __builtin_amdgcn_readfirstlane(t.pwt);
+        lt.npix = live ? __builtin_amdgcn_readfirstlane(t.npix) : 0;
+        lt.rcp_pwt = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, t.rcp_pwt)));
+    };
+    auto advance_load_cursor = [&]() __attribute__((always_inline)) {
+        if (++l_cb == p.ncb) {
+            l_cb = 0;
+            l_tile += grid;
+            load_tile_patch();
+        }
+    };
+    auto load_chunk = [&](int i) __attribute__((always_inline)) {
+        const int pix = my_pix + i * (NT / PL);
+        const int ch = l_cb * Cfg::kCB + my_c;
+        uint32_t off = patch_pixel_offset_u32(g, lt, pix, p.C, kPatchInvalidOffset);
+        off = (ch < p.C) ? off : kPatchInvalidOffset;            // a tap's channel padding reads as zero
+        off += (off != kPatchInvalidOffset) ? (uint32_t)ch : 0u;
+        a_reg[i] = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, (int)off, 0, 0);   // out of range reads 0
+    };
+    // trim + flip to signed + write into the patch buffer at `buf`
+    auto stage_chunk = [&](int i, uint8_t* buf) __attribute__((always_inline)) {
+        v4u v = a_reg[i];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = trim4_kind<KIND>(v[j], p.luts) ^ 0x80808080u;
+        const int pix = my_pix + i * (NT / PL);
+        uint8_t* dst = (pix < stage_npix) ? buf + my_loff + i * (NT / PL) * kChunk : lds + dummy_off;
+        *reinterpret_cast<v4u*>(dst) = v;
+    };
+
+    // ---- compute cursor ----
+    int c_tile = (int)blockIdx.x, c_cb = 0, c_tm = 0, c_tn = 0;
+    int c_pwt16 = 0;                              // bytes per patch row inside a plane
+    int32_t fbase[FM];                            // patch byte offset of this lane's pixel (tap 0,0) per fragment
+    auto setup_compute_tile = [&]() __attribute__((always_inline)) {
+        c_tm = c_tile / p.tiles_n;
+        c_tn = c_tile - c_tm * p.tiles_n;
+        const TilePatch t = tile_patch(g, c_tm * kPatchTM);
+        c_pwt16 = t.pwt * kChunk;
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            int m = c_tm * kPatchTM + wm * Cfg::kWTM + i * 32 + l32;
+            m = m < g.M ? m : g.M - 1;
+            fbase[i] = patch_pixel_of_output(g, t, m) * kChunk + lhi * p.plane_stride;
+        }
+    };
+
+    // fragment cursor: which (kh, kw, 64-channel sub-block) the next fragment read is for
+    int f_j = 0, f_kw = 0, f_kh = 0, f_off = 0;
+    auto advance_frag_cursor = [&]() __attribute__((always_inline)) {
+        const int sub = 4 * p.plane_stride;
+        ++f_j;
+        f_off += sub;
+        const bool wj = f_j == CBS;
+        f_j = wj ? 0 : f_j;
+        f_off += wj ? kChunk - CBS * sub : 0;
+        f_kw += wj ? 1 : 0;
+        const bool wk = f_kw == g.KW;
+        f_kw = wk ? 0 : f_kw;
+        f_off += wk ? c_pwt16 - g.KW * kChunk : 0;
+        f_kh += wk ? 1 : 0;
+        const bool wh = f_kh == g.KH;              // past the unit's last step: wrap (the read is not used)
+        f_kh = wh ? 0 : f_kh;
+        f_off = wh ? 0 : f_off;
+    };
+    auto load_frags = [&](v4i (&af)[2][FM], const uint8_t* buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+                af[ks][i] = *reinterpret_cast<const v4i*>(buf + fbase[i] + f_off + ks * 2 * p.plane_stride);
+    };
+
+    // ---- weight cursor: runs two steps ahead of the multiplications, across units and tiles.
+    //      Lane (l32, lhi) of fragment j, half ks holds w[n0 + wn*WTN + j*32 + l32][16 bytes at 16*(2*ks+lhi)];
+    //      the lane part of the address is fixed, everything else is uniform ----
+    const __amdgpu_buffer_rsrc_t wrsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.wpk), 0, (int)p.w_bytes, 0x00020000);
+    const int wlane = (lhi * p.Np + wn * Cfg::kWTN + l32) * kChunk;
+    const int w_half = 2 * p.Np * kChunk;         // bytes between the two 32-channel halves of a step
+    const int grid_n = grid % p.tiles_n;
+    int b_s = 0, b_cb = 0, b_tn = (int)blockIdx.x % p.tiles_n;
+    auto next_b_offset = [&]() __attribute__((always_inline)) -> int {
+        const int kidx = (b_s / CBS) * p.ksteps_tap + b_cb * CBS + (b_s % CBS);
+        const int off = b_tn * TN * kChunk + kidx * 2 * w_half;
+        ++b_s;
+        const bool ws = b_s == p.nsteps;
+        b_s = ws ? 0 : b_s;
+        b_cb += ws ? 1 : 0;
+        const bool wc = b_cb == p.ncb;
+        b_cb = wc ? 0 : b_cb;
+        b_tn += wc ? grid_n : 0;
+        b_tn -= b_tn >= p.tiles_n ? p.tiles_n : 0;
+        return off;
+    };
+    auto load_b = [&](v4i (&br)[FN], int wstep, int ks) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+            br[j] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, wlane, wstep + ks * w_half + j * 32 * kChunk, 0));
+    };
+
+    v16i c[FM][FN];
+    auto zero_acc = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) c[i][j][v] = 0;
+    };
+    v4i b_reg[2][2][FN];          // weights of the current and the next step: [step parity][half][fragment]
+    v4i a_frag[2][2][FM];         // activation fragments: [step parity][half][fragment]
+
+    // ---- prologue: unit 0 staged, unit 1 requested, two weight steps requested ----
+    load_tile_patch();
+#pragma unroll
+    for (int i = 0; i < AC; ++i) load_chunk(i);
+    {
+        const int w0 = next_b_offset();
+        load_b(b_reg[0][0], w0, 0);
+        load_b(b_reg[0][1], w0, 1);
+        const int w1 = next_b_offset();
+        load_b(b_reg[1][0], w1, 0);
+        load_b(b_reg[1][1], w1, 1);
+    }
+    stage_npix = lt.npix;
+#pragma unroll
+    for (int i = 0; i < AC; ++i) stage_chunk(i, lds);
+    advance_load_cursor();
+    stage_npix = lt.npix;                         // unit 1 is staged while unit 0 is multiplied
+#pragma unroll
+    for (int i = 0; i < AC; ++i) load_chunk(i);
+    advance_load_cursor();
+    setup_compute_tile();
+    zero_acc();
+    __syncthreads();
+
+    // One reduction step (64 channels of one tap).  A >= 0: the step also trims and stages chunks
+    // 2A and 2A+1 of the next unit and requests the same chunks of the unit after it.  The two
+    // scheduling regions keep the compiler from sinking the loads next to their uses.
+    auto step = [&](auto A_, v4i (&cur)[2][FM], v4i (&nxt)[2][FM], v4i (&br)[2][FN], const uint8_t* rbuf, uint8_t* sbuf) __attribute__((always_inline)) {
+        constexpr int A = decltype(A_)::value;
+        advance_frag_cursor();
+        load_frags(nxt, rbuf);
+        const int wstep = next_b_offset();
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+                c[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur[0][i], br[0][j], c[i][j], 0, 0, 0);
+        load_b(br[0], wstep, 0);
+        if constexpr (A >= 0) {
+            stage_chunk(2 * A, sbuf);
+            load_chunk(2 * A);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+                c[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur[1][i], br[1][j], c[i][j], 0, 0, 0);
+        load_b(br[1], wstep, 1);
+        if constexpr (A >= 0 && 2 * A + 1 < AC) {
+            stage_chunk(2 * A + 1, sbuf);
+            load_chunk(2 * A + 1);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // One unit.  P: parity of the global step count at its start; step s uses fragment and weight
+    // slot (P + s) & 1.  The first U0 steps are unrolled (the AS staging steps, plus one plain step if
+    // that is what makes the rest an even count); the rest runs as pairs.  Keeping the structure this
+    // rigid lets every wait for an outstanding load be exact.
+    constexpr bool ODD = Cfg::kOddSteps;
+    constexpr int U0 = Cfg::kUnrolled;
+    auto run_unit = [&](auto P_, const uint8_t* rbuf, uint8_t* sbuf) __attribute__((always_inline)) {
+        constexpr int P = decltype(P_)::value;
+        f_j = f_kw = f_kh = f_off = 0;
+        load_frags(a_frag[P], rbuf);
+        auto head = [&](auto self, auto s_) __attribute__((always_inline)) {
+            constexpr int s0 = decltype(s_)::value;
+            if constexpr (s0 < U0) {
+                step(int_c<(s0 < AS ? s0 : -1)>{}, a_frag[(P + s0) & 1], a_frag[(P + s0 + 1) & 1], b_reg[(P + s0) & 1], rbuf, sbuf);
+                self(self, int_c<s0 + 1>{});
+            }
+        };
+        head(head, int_c<0>{});
+        constexpr int Q = (P + U0) & 1;
+        for (int rem = p.nsteps - U0; rem > 0; rem -= 2) {
+            step(int_c<-1>{}, a_frag[Q], a_frag[Q ^ 1], b_reg[Q], rbuf, sbuf);
+            step(int_c<-1>{}, a_frag[Q ^ 1], a_frag[Q], b_reg[Q ^ 1], rbuf, sbuf);
+        }
+    };
+
+    // End of a unit: results out if it was the tile's last channel block, barrier, cursors forward.
+    int ubuf = 0;
+    auto boundary = [&]() __attribute__((always_inline)) {
+        ubuf ^= 1;
+        if (c_cb == p.ncb - 1) {
+            // ---- epilogue: undo the -128 offset, store int32 and/or dequantised fp32 ----
+            // Register v of fragment (i, j) is pixel 8*(v/4) + 4*lhi + v%4, channel l32: each store
+            // instruction writes two full 128-byte runs of consecutive channels.
+            const int64_t m0 = (int64_t)c_tm * kPatchTM;
+            const int n0 = c_tn * TN;
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                const int n = n0 + wn * Cfg::kWTN + j * 32 + l32;
+                if (n >= p.N) continue;
+                const int32_t corr = 128 * p.colsum[n];
+                const float sc = p.out ? p.scale[n] : 0.0f;
+#pragma unroll
+                for (int i = 0; i < FM; ++i) {
+                    const int64_t mb = m0 + wm * Cfg::kWTM + i * 32 + 4 * lhi;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int64_t m = mb + 8 * (v / 4) + (v % 4);
+                        if (m >= g.M) continue;
+                        const int32_t r = c[i][j][v] + corr;
+                        const int64_t o = m * p.N + n;
+                        if (p.acc) p.acc[o] = r;
+                        if (p.out) p.out[o] = __fmul_rn((float)r, sc);
+                    }
+                }
+            }
+            zero_acc();
+        }
+        __syncthreads();
+        if (++c_cb == p.ncb) {
+            c_cb = 0;
+            c_tile += grid;
+            if (c_tile < ntiles) setup_compute_tile();
+        }
+        stage_npix = lt.npix;                     // the unit requested during the last unit is staged in the next
+        advance_load_cursor();
+    };
+
+    while (true) {
+        run_unit(int_c<0>{}, lds + ubuf * buf_bytes, lds + (ubuf ^ 1) * buf_bytes);
+        boundary();
+        if (c_tile >= ntiles) break;
+        if constexpr (ODD) {       // an odd number of steps flips the slot parity: alternate two copies
+            run_unit(int_c<1>{}, lds + ubuf * buf_bytes, lds + (ubuf ^ 1) * buf_bytes);
+            boundary();
+            if (c_tile >= ntiles) break;
+        }
+    }
+}
+
+constexpr int kLdsPerCu = 160 * 1024;
+
+// `p` carries everything except plane_stride and the tile counts; npix_max bounds TilePatch::npix.
+template <class Cfg, int KIND>
+sparq_status launch_patch_cfg(const PatchParams& p, int npix_max, hipStream_t s) {
+    PatchParams q = p;
+    q.plane_stride = patch_plane_stride(npix_max, Cfg::kPlanes);
+    const int lds_bytes = 2 * Cfg::kPlanes * q.plane_stride + kChunk;     // two patch buffers + the dummy chunk
+    if (npix_max > Cfg::kMaxPix || lds_bytes > kLdsPerCu || q.nsteps < Cfg::kUnrolled ||
+        ((q.nsteps - Cfg::kUnrolled) & 1))
+        return SPARQ_EUNSUPPORTED;
+    auto kern = conv_patch_kernel<Cfg, KIND>;
+    static int lds_set = 0;
+    if (lds_bytes > lds_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                lds_bytes) != hipSuccess)
+            return SPARQ_ELAUNCH;
+        lds_set = lds_bytes;
+    }
+    q.tiles_m = (p.g.M + kPatchTM - 1) / kPatchTM;
+    q.tiles_n = (p.N + Cfg::kTN - 1) / Cfg::kTN;
+    const int64_t tiles = (int64_t)q.tiles_m * q.tiles_n;
+    if (tiles > 0x7FFFFFFF) return SPARQ_EUNSUPPORTED;
+    int per_cu = kLdsPerCu / lds_bytes;
+    if (per_cu > Cfg::kWgPerCu) per_cu = Cfg::kWgPerCu;
+    const int64_t resident = (int64_t)device_cu_count() * per_cu;
+    const unsigned blocks = (unsigned)(tiles < resident ? tiles : resident);
+    kern<<<blocks, Cfg::kThreads, lds_bytes, s>>>(q);
+    return launch_status();
+}
+
+template <class Cfg>
+sparq_status launch_patch_kind(TrimKind kind, const PatchParams& p, int npix_max, hipStream_t s) {
+    switch (kind) {
+        case kTrimNone: return launch_patch_cfg<Cfg, kTrimNone>(p, npix_max, s);
+#ifndef SPARQ_DEV_FEW_KINDS
+        case kTrimFloor: return launch_patch_cfg<Cfg, kTrimFloor>(p, npix_max, s);
+        case kTrimFloorPair: return launch_patch_cfg<Cfg, kTrimFloorPair>(p, npix_max, s);
+        case kTrimFloorPairWide: return launch_patch_cfg<Cfg, kTrimFloorPairWide>(p, npix_max, s);
+        case kTrimRound: return launch_patch_cfg<Cfg, kTrimRound>(p, npix_max, s);
+        case kTrimRound4: return launch_patch_cfg<Cfg, kTrimRound4>(p, npix_max, s);
+        case kTrimRoundPairWide: return launch_patch_cfg<Cfg, kTrimRoundPairWide>(p, npix_max, s);
+#endif
+        case kTrimRoundPair4: return launch_patch_cfg<Cfg, kTrimRoundPair4>(p, npix_max, s);
+        default: return SPARQ_EUNSUPPORTED;
+    }
+}
+
+// One translation unit per tile shape instantiates every trim variant and exports a launcher.
+typedef sparq_status (*PatchLauncher)(TrimKind, const PatchParams&, int, hipStream_t);
+#define SPARQ_DECLARE_PATCH(name) sparq_status name(TrimKind kind, const PatchParams& p, int npix_max, hipStream_t s)
+SPARQ_DECLARE_PATCH(launch_patch_n64_a2c1);
+SPARQ_DECLARE_PATCH(launch_patch_n64_a4c1);
+SPARQ_DECLARE_PATCH(launch_patch_n64_a8c1);
+SPARQ_DECLARE_PATCH(launch_patch_n64_a4c2);
+SPARQ_DECLARE_PATCH(launch_patch_n64_a8c4);
+SPARQ_DECLARE_PATCH(launch_patch_n128_a2c1);
+SPARQ_DECLARE_PATCH(launch_patch_n128_a4c1);
+SPARQ_DECLARE_PATCH(launch_patch_n128_a8c1);
+SPARQ_DECLARE_PATCH(launch_patch_n128_a4c2);
+SPARQ_DECLARE_PATCH(launch_patch_n128_a8c4);
+SPARQ_DECLARE_PATCH(launch_patch_n256_a2c1);
+SPARQ_DECLARE_PATCH(launch_patch_n256_a4c1);
+SPARQ_DECLARE_PATCH(launch_patch_n256_a8c1);
+SPARQ_DECLARE_PATCH(launch_patch_n256_a4c2);
+SPARQ_DECLARE_PATCH(launch_patch_n256_a8c4);
+
+}  // namespace sparq

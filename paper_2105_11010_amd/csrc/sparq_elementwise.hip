@@ -153,14 +153,14 @@ __global__ __launch_bounds__(kEwThreads) void dequant_scalar_kernel(const int32_
 // ---- weight packing ----------------------------------------------------------
 // packed[w_off + ((kb*4 + kc)*Np + n)*16 + j] = w[n][tap][c + j]  with  k = kb*64 + kc*16 = tap*Cp + c
 __global__ __launch_bounds__(kEwThreads) void pack_weights_kernel(const int8_t* __restrict__ w, uint4* __restrict__ dst,
-                                                                  int N, int Np, int C, int Cp, int taps, int Kp) {
+                                                                  int N, int Np, int C, int Cq, int taps, int Kp) {
     const int64_t total = (int64_t)(Kp / kChunk) * Np;
     const int64_t stride = (int64_t)gridDim.x * kEwThreads;
     for (int64_t i = (int64_t)blockIdx.x * kEwThreads + threadIdx.x; i < total; i += stride) {
         const int n = (int)(i % Np);
         const int k = (int)(i / Np) * kChunk;
-        const int tap = k / Cp;
-        const int c = k - tap * Cp;
+        const int tap = k / Cq;
+        const int c = k - tap * Cq;
         uint32_t v[4] = {0, 0, 0, 0};
         if (n < N && tap < taps) {
             const int8_t* src = w + ((int64_t)n * taps + tap) * C + c;
@@ -243,7 +243,7 @@ extern "C" sparq_status sparq_pack_weights(const int8_t* w, const sparq_conv_des
     weight_colsum_kernel<<<g.Np, 64, 0, s>>>(w, reinterpret_cast<int32_t*>(base), g.N, g.Np, g.K);
     const int64_t chunks = (int64_t)(g.Kp / kChunk) * g.Np;
     pack_weights_kernel<<<ew_grid(chunks, kEwThreads), kEwThreads, 0, s>>>(
-        w, reinterpret_cast<uint4*>(base + g.w_off), g.N, g.Np, g.C, g.Cp, g.KH * g.KW, g.Kp);
+        w, reinterpret_cast<uint4*>(base + g.w_off), g.N, g.Np, g.C, g.Cq, g.KH * g.KW, g.Kp);
     return launch_status();
 }
 

@@ -137,15 +137,63 @@ SHAPES = [
 ]
 
 
+# The library holds two convolution kernels (an im2col-gather form and an input-patch form) and
+# picks one per layer; SPARQ_PATH forces either where the layer is eligible, so both are compared
+# with the oracle on every shape.
+@pytest.fixture(params=["auto", "gather", "patch"])
+def path(request, monkeypatch):
+    monkeypatch.delenv("SPARQ_PATH", raising=False)
+    monkeypatch.delenv("SPARQ_PATCH_TN", raising=False)
+    monkeypatch.delenv("SPARQ_TILE", raising=False)
+    if request.param != "auto":
+        monkeypatch.setenv("SPARQ_PATH", request.param)
+    return request.param
+
+
 @pytest.mark.parametrize("layer", SHAPES, ids=lambda l: l.name)
 @pytest.mark.parametrize("mode", [S.Mode(4, S.OPT5, 1, 1), S.Mode(4, S.OPT3, 0, 1), S.Mode(2, S.OPT7_2B, 1, 1), S.PLAIN8],
                          ids=lambda m: m.label)
-def test_conv_shapes(sq, oracle, layer, mode):
+def test_conv_shapes(sq, oracle, layer, mode, path):
     check_layer(sq, oracle, layer, mode, seed_cfg=8)
 
 
+# Shapes chosen for the input-patch kernel: tiles that span several image rows and several images,
+# one-row tiles, every staging variant (64/128/256-channel units), several output-channel tiles.
+PATCH_SHAPES = [
+    S.ConvLayer("p_3x3_56_c64_n64", 2, 56, 56, 64, 64, 3, 3, (1, 1), (1, 1)),
+    S.ConvLayer("p_3x3_8x8_c128_n300", 9, 8, 8, 128, 300, 3, 3, (1, 1), (1, 1)),
+    S.ConvLayer("p_3x3_7x7_c64_n96", 11, 7, 7, 64, 96, 3, 3, (1, 1), (1, 1)),
+    S.ConvLayer("p_3x3_wide_row", 1, 5, 300, 64, 40, 3, 3, (1, 1), (1, 1)),
+    S.ConvLayer("p_5x5_c48", 3, 20, 20, 48, 70, 5, 5, (1, 1), (2, 2)),
+    S.ConvLayer("p_1x3_c384", 5, 8, 8, 384, 130, 1, 3, (1, 1), (0, 1)),
+    S.ConvLayer("p_3x1_c96", 5, 8, 8, 96, 64, 3, 1, (1, 1), (1, 0)),
+    S.ConvLayer("p_1x1_c64", 1, 37, 41, 64, 256),
+    S.ConvLayer("p_1x1_c128", 2, 30, 30, 128, 192),
+    S.ConvLayer("p_1x1_c256", 1, 50, 27, 256, 72),
+    S.ConvLayer("p_1x1_c768", 1, 33, 33, 768, 128),
+    S.ConvLayer("p_1x1_c80", 1, 19, 23, 80, 50),
+    S.ConvLayer("p_3x3_s2_small", 6, 9, 9, 64, 32, 3, 3, (2, 2), (1, 1)),
+    S.ConvLayer("p_3x3_p2_dilated_pad", 2, 6, 6, 64, 16, 3, 3, (1, 1), (2, 2)),
+    S.ConvLayer("p_2x2_even_taps", 2, 10, 10, 64, 16, 2, 2, (1, 1), (0, 0)),
+]
+
+
+@pytest.mark.parametrize("layer", PATCH_SHAPES, ids=lambda l: l.name)
+@pytest.mark.parametrize("mode", [S.Mode(4, S.OPT5, 1, 1), S.Mode(3, S.OPT6_3B, 0, 1)], ids=lambda m: m.label)
+def test_conv_patch_shapes(sq, oracle, layer, mode, path):
+    check_layer(sq, oracle, layer, mode, seed_cfg=9)
+
+
+@pytest.mark.parametrize("tn", ["64", "128", "256"])
+def test_conv_patch_channel_tiles(sq, oracle, monkeypatch, tn):
+    """Every output-channel tile width of the input-patch kernel on the same layer."""
+    monkeypatch.setenv("SPARQ_PATH", "patch")
+    monkeypatch.setenv("SPARQ_PATCH_TN", tn)
+    check_layer(sq, oracle, S.ConvLayer("p_tn", 3, 14, 14, 128, 520, 3, 3, (1, 1), (1, 1)), S.Mode(4, S.OPT5, 1, 1), seed_cfg=9)
+
+
 @pytest.mark.parametrize("mode", MODES_N4 + MODES_LOW + MODES_ODD, ids=lambda m: m.label + f"-{m.shift_mask:#x}")
-def test_conv_all_modes(sq, oracle, mode):
+def test_conv_all_modes(sq, oracle, mode, path):
     check_layer(sq, oracle, S.ConvLayer("3x3_modes", 1, 14, 14, 64, 48, 3, 3, (1, 1), (1, 1), index=3), mode)
 
 
