@@ -94,9 +94,12 @@ size_t sparq_packed_bytes(const sparq_conv_desc *desc);
 sparq_status sparq_pack_weights(const int8_t *w, const sparq_conv_desc *desc,
                                 void *packed, size_t packed_bytes, void *stream);
 
-/* Scratch the convolution needs for this descriptor and mode (0 for channel
- * counts that are a multiple of 16; otherwise room for a trimmed, channel-padded
- * copy of the input). */
+/* Scratch the convolution may need for this descriptor and mode on the current
+ * device: room for a trimmed, channel-padded copy of the input when C is not a
+ * multiple of 16, plus M*N int32 partial sums for layers so small that the
+ * reduction is split over several workgroups (used only when acc is NULL).
+ * 0 for most layers.  The buffer is overwritten by every call that uses it;
+ * calls that share one workspace must not overlap. */
 size_t sparq_workspace_bytes(const sparq_conv_desc *desc, const sparq_mode *mode);
 
 /* Eq. 1 over trimmed activations as an implicit GEMM:
@@ -105,8 +108,9 @@ size_t sparq_workspace_bytes(const sparq_conv_desc *desc, const sparq_mode *mode
  *   out[m][n] = (float)acc[m][n] * scale[n].
  * At least one of acc / out must be given; out requires scale.  x must be
  * 16-byte aligned, acc/out 16-byte aligned, packed_w as produced by
- * sparq_pack_weights for the same desc.  workspace may be NULL when
- * sparq_workspace_bytes() is 0.  Rejected with SPARQ_EINVAL when K = KH*KW*C
+ * sparq_pack_weights for the same desc.  workspace (256-byte aligned, at least
+ * sparq_workspace_bytes() bytes) may be NULL when that size is 0; too small a
+ * buffer returns SPARQ_EWORKSPACE before anything is launched.  Rejected with SPARQ_EINVAL when K = KH*KW*C
  * is large enough for 255*127*K to leave the int32 range. */
 sparq_status sparq_conv_gemm(const uint8_t *x, const void *packed_w,
                              const sparq_conv_desc *desc, const sparq_mode *mode,

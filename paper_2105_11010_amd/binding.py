@@ -14,7 +14,8 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libsparq.so")
+# SPARQ_LIBRARY points at another build of the same library (A/B comparisons); default: the in-tree build
+LIB_PATH = os.environ.get("SPARQ_LIBRARY") or os.path.join(_HERE, "libsparq.so")
 
 SPARQ_OK, SPARQ_EINVAL, SPARQ_EUNSUPPORTED, SPARQ_EWORKSPACE, SPARQ_ELAUNCH = range(5)
 

@@ -126,4 +126,8 @@ inline int device_cu_count() {
 sparq_status launch_trim_pad(const uint8_t* x, uint8_t* xp, int64_t pixels, int C, int Cp,
                              const sparq_mode* mode, hipStream_t stream);
 
+
+// Implemented in sparq_elementwise.hip: kernel-based clear of a 16-byte aligned buffer.
+sparq_status launch_zero(void* dst, size_t bytes, hipStream_t stream);
+
 }  // namespace sparq

@@ -35,12 +35,14 @@ TileLauncher pick_tile(const ConvGeom& g) {
 }
 
 // ---- input-patch kernel: eligibility and variant choice --------------------------------------
-struct PatchVariant { int tn, ac, cbs; PatchLauncher fn; };
+struct PatchVariant { int tn, ac, cbs; PatchLauncher fn; PatchLauncher fn_split; };   // fn_split: null if not built
 const PatchVariant kPatchVariants[] = {
+    {64, 12, 1, launch_patch_n64_a12c1}, {128, 12, 1, launch_patch_n128_a12c1}, {256, 12, 1, launch_patch_n256_a12c1},
     {64, 2, 1, launch_patch_n64_a2c1},   {64, 4, 1, launch_patch_n64_a4c1},   {64, 8, 1, launch_patch_n64_a8c1},
     {64, 4, 2, launch_patch_n64_a4c2},   {64, 8, 4, launch_patch_n64_a8c4},
-    {128, 2, 1, launch_patch_n128_a2c1}, {128, 4, 1, launch_patch_n128_a4c1}, {128, 8, 1, launch_patch_n128_a8c1},
-    {128, 4, 2, launch_patch_n128_a4c2}, {128, 8, 4, launch_patch_n128_a8c4},
+    {128, 2, 1, launch_patch_n128_a2c1}, {128, 4, 1, launch_patch_n128_a4c1, launch_patch_split_n128_a4c1},
+    {128, 8, 1, launch_patch_n128_a8c1, launch_patch_split_n128_a8c1},
+    {128, 4, 2, launch_patch_n128_a4c2}, {128, 8, 4, launch_patch_n128_a8c4, launch_patch_split_n128_a8c4},
     {256, 2, 1, launch_patch_n256_a2c1}, {256, 4, 1, launch_patch_n256_a4c1}, {256, 8, 1, launch_patch_n256_a8c1},
     {256, 4, 2, launch_patch_n256_a4c2}, {256, 8, 4, launch_patch_n256_a8c4},
 };
@@ -97,7 +99,7 @@ bool plan_patch(const ConvGeom& g, PatchGeom* pg, int* npix, int* ac, int* cbs) 
     const int ksteps = g.Cq / kStepK;
     // candidates (chunks per lane, channel block / 64): larger channel blocks first for 1x1 layers,
     // the smallest staging that holds the patch otherwise
-    static const int cand[5][2] = {{8, 4}, {4, 2}, {2, 1}, {4, 1}, {8, 1}};
+    static const int cand[6][2] = {{8, 4}, {4, 2}, {2, 1}, {4, 1}, {8, 1}, {12, 1}};
     for (const auto& c : cand) {
         const int a = c[0], cb = c[1];
         if (ksteps % cb) continue;
@@ -116,17 +118,42 @@ bool plan_patch(const ConvGeom& g, PatchGeom* pg, int* npix, int* ac, int* cbs) 
 // Output-channel tile of the patch kernel: 64 for narrow layers; otherwise 128 (two workgroups per
 // CU hide each other's latencies), 256 only for long reductions over a multiple of 256 channels
 // with enough tiles to fill the chip.  SPARQ_PATCH_TN=<n> (a tuning knob) forces one.
-PatchLauncher pick_patch(const ConvGeom& g, int ac, int cbs) {
+const PatchVariant* pick_patch(const ConvGeom& g, int ac, int cbs, int npix, bool forced) {
     const int64_t tiles_m = (g.M + kPatchTM - 1) / kPatchTM;
     int tn = g.N <= 64 ? 64 : 128;
     if (g.N >= 512 && g.N % 256 == 0 && g.K >= 2048 && tiles_m * (g.N / 256) >= device_cu_count()) tn = 256;
+    // A patch so large that only one workgroup fits a CU's LDS (strided 3x3 layers on large
+    // images): the two-workgroup tiles lose their point; wide layers take the 256 tile, narrow
+    // ones are left to the gather kernel.
+    if (2 * 4 * cbs * patch_plane_stride(npix, 4 * cbs) > kLdsPerCu / 2) {
+        if (g.N >= 256) tn = 256;
+        else if (!forced) return nullptr;
+    }
     if (const char* e = getenv("SPARQ_PATCH_TN")) {
         const int v = atoi(e);
         if ((v == 64 || v == 128 || v == 256) && tile_fits(v, g)) tn = v;
     }
     for (const PatchVariant& v : kPatchVariants)
-        if (v.tn == tn && v.ac == ac && v.cbs == cbs) return v.fn;
+        if (v.tn == tn && v.ac == ac && v.cbs == cbs) return &v;
     return nullptr;
+}
+
+// Split reduction: when a layer has far fewer tiles than the chip has room for workgroups, a
+// tile's channel blocks are spread over 2^k workgroups that add their int32 partial sums with
+// atomics (exact: integer addition commutes).  SPARQ_SPLIT=<k> (a tuning knob) forces k.
+int pick_split_log2(const ConvGeom& g, const PatchVariant& v, int ncb) {
+    if (!v.fn_split) return 0;
+    const int64_t tiles = (g.M + kPatchTM - 1) / kPatchTM * ((g.N + v.tn - 1) / v.tn);
+    const int64_t slots = (int64_t)device_cu_count() * 2;
+    int lg = 0;
+    // worth it only while the chip stays at most half full: the cleared buffer and the extra
+    // dequantisation pass cost two more small launches
+    while (lg < 3 && ncb % (2 << lg) == 0 && tiles * (2 << lg) * 2 <= slots) ++lg;
+    if (const char* e = getenv("SPARQ_SPLIT")) {
+        const int v = atoi(e);
+        if (v >= 0 && v <= 3 && ncb % (1 << v) == 0) lg = v;
+    }
+    return lg;
 }
 
 // 1x1 stride-1 layers with a long reduction have nothing to reuse between taps; when they also
@@ -140,13 +167,41 @@ bool prefer_gather(const ConvGeom& g) {
     return tiles >= device_cu_count() && round_up(g.N, tn) * 100 <= (int64_t)g.N * 115;
 }
 
+// Everything the entry points decide before launching.
+struct ConvPlan {
+    bool patch = false;
+    const PatchVariant* variant = nullptr;
+    PatchGeom pg{};
+    int npix = 0, ac = 0, cbs = 0, split_log2 = 0;
+    size_t pad_bytes = 0;       // channel-padded copy of x (channel counts that are not a multiple of 16)
+    size_t split_bytes = 0;     // int32 partial sums of a split reduction when the caller passes no acc
+};
+
+ConvPlan make_plan(const ConvGeom& g) {
+    ConvPlan pl;
+    if (g.Cp != g.C) pl.pad_bytes = (size_t)round_up((int64_t)g.B * g.H * g.W * g.Cp, 256);
+    const char* path = getenv("SPARQ_PATH");
+    const bool force_gather = path && !strcmp(path, "gather"), force_patch = path && !strcmp(path, "patch");
+    ConvGeom gk = g;
+    gk.C = gk.Cp;                                                // what the kernel sees after the padding pre-pass
+    if (!force_gather && (force_patch || !prefer_gather(g)) && plan_patch(gk, &pl.pg, &pl.npix, &pl.ac, &pl.cbs)) {
+        pl.variant = pick_patch(g, pl.ac, pl.cbs, pl.npix, force_patch);
+        if (pl.variant) {
+            pl.patch = true;
+            pl.split_log2 = pick_split_log2(g, *pl.variant, g.Cq / kStepK / pl.cbs);
+            if (pl.split_log2) pl.split_bytes = (size_t)round_up(g.M * g.N * 4, 256);
+        }
+    }
+    return pl;
+}
+
 }  // namespace
 
 extern "C" size_t sparq_workspace_bytes(const sparq_conv_desc* desc, const sparq_mode* mode) {
     ConvGeom g;
     if (!conv_geom(desc, &g) || !mode_valid(mode)) return 0;
-    if (g.Cp == g.C) return 0;
-    return (size_t)round_up((int64_t)g.B * g.H * g.W * g.Cp, 256);
+    const ConvPlan pl = make_plan(g);
+    return pl.pad_bytes + pl.split_bytes;
 }
 
 extern "C" sparq_status sparq_conv_gemm(const uint8_t* x, const void* packed_w, const sparq_conv_desc* desc,
@@ -160,6 +215,13 @@ extern "C" sparq_status sparq_conv_gemm(const uint8_t* x, const void* packed_w, 
         (scale && !aligned(scale, 16)))
         return SPARQ_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    const ConvPlan pl = make_plan(g);
+    const bool split = pl.patch && pl.split_log2 > 0;
+    const size_t need = pl.pad_bytes + ((split && !acc) ? pl.split_bytes : 0);
+    if (need) {
+        if (!workspace || !aligned(workspace, 256)) return SPARQ_EINVAL;
+        if (workspace_bytes < need) return SPARQ_EWORKSPACE;
+    }
 
     const uint8_t* xin = x;
     TrimKind kind = trim_kind(mode);
@@ -168,9 +230,6 @@ extern "C" sparq_status sparq_conv_gemm(const uint8_t* x, const void* packed_w, 
         // Channel counts that are not a multiple of 16: trim into a channel-padded copy
         // first (pairs stay inside the row; padded channels are zeros with zero weights),
         // then contract the copy without further trimming.
-        const size_t need = sparq_workspace_bytes(desc, mode);
-        if (!workspace || !aligned(workspace, 256)) return SPARQ_EINVAL;
-        if (workspace_bytes < need) return SPARQ_EWORKSPACE;
         x_bytes = (size_t)g.B * g.H * g.W * g.Cp;
         if (x_bytes >= kInvalidOffset) return SPARQ_EUNSUPPORTED;
         const sparq_status st = launch_trim_pad(x, static_cast<uint8_t*>(workspace), (int64_t)g.B * g.H * g.W, g.C,
@@ -183,28 +242,32 @@ extern "C" sparq_status sparq_conv_gemm(const uint8_t* x, const void* packed_w, 
 
     // Preferred: the input-patch kernel (activations loaded and trimmed once per tile and channel
     // block).  SPARQ_PATH=gather|patch (a tuning knob, not part of the interface) forces one of the two kernels.
-    const char* path = getenv("SPARQ_PATH");
-    PatchGeom pg;
-    int npix = 0, ac = 0, cbs = 0;
-    ConvGeom gk = g;
-    gk.C = gk.Cp;                                                // what the kernel sees after the padding pre-pass
-    const bool force_gather = path && !strcmp(path, "gather"), force_patch = path && !strcmp(path, "patch");
-    if (!force_gather && (force_patch || !prefer_gather(g)) && plan_patch(gk, &pg, &npix, &ac, &cbs)) {
-        if (PatchLauncher fn = pick_patch(g, ac, cbs)) {
-            PatchParams q{};
-            q.x = xin;
-            q.wpk = static_cast<const uint8_t*>(packed_w) + g.w_off;
-            q.colsum = static_cast<const int32_t*>(packed_w);
-            q.acc = acc; q.scale = scale; q.out = out;
-            q.x_bytes = (uint32_t)x_bytes;
-            q.w_bytes = (uint32_t)((size_t)g.Kp * g.Np);
-            q.N = g.N; q.Np = g.Np; q.C = g.Cp;
-            q.ksteps_tap = g.Cq / kStepK;
-            q.ncb = q.ksteps_tap / cbs;
-            q.nsteps = g.KH * g.KW * cbs;
-            q.g = pg;
-            q.luts = make_luts(mode->window_bits, mode->shift_mask);
-            const sparq_status st = fn(kind, q, npix, s);
+    if (pl.patch) {
+        PatchParams q{};
+        q.x = xin;
+        q.wpk = static_cast<const uint8_t*>(packed_w) + g.w_off;
+        q.colsum = static_cast<const int32_t*>(packed_w);
+        q.acc = acc; q.scale = scale; q.out = out;
+        q.x_bytes = (uint32_t)x_bytes;
+        q.w_bytes = (uint32_t)((size_t)g.Kp * g.Np);
+        q.N = g.N; q.Np = g.Np; q.C = g.Cp;
+        q.ksteps_tap = g.Cq / kStepK;
+        q.ncb = (q.ksteps_tap / pl.cbs) >> pl.split_log2;
+        q.split_log2 = pl.split_log2;
+        q.nsteps = g.KH * g.KW * pl.cbs;
+        q.g = pl.pg;
+        q.luts = make_luts(mode->window_bits, mode->shift_mask);
+        if (split) {
+            // partial sums are added into a cleared int32 buffer; the fp32 output is a second pass over it
+            int32_t* sum = acc ? acc : reinterpret_cast<int32_t*>(static_cast<uint8_t*>(workspace) + pl.pad_bytes);
+            sparq_status st = launch_zero(sum, (size_t)round_up(g.M * g.N * 4, 16), s);
+            if (st != SPARQ_OK) return st;
+            q.acc = sum; q.scale = nullptr; q.out = nullptr;
+            st = pl.variant->fn_split(kind, q, pl.npix, s);
+            if (st == SPARQ_OK && out) st = sparq_dequant(sum, scale, out, g.M, g.N, stream);
+            if (st != SPARQ_EUNSUPPORTED) return st;
+        } else {
+            const sparq_status st = pl.variant->fn(kind, q, pl.npix, s);
             if (st != SPARQ_EUNSUPPORTED) return st;
         }
     }

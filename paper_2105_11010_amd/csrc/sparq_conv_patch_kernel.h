@@ -43,11 +43,12 @@ struct PatchParams {
     float* out;              // [M][N] or null
     uint32_t x_bytes, w_bytes;
     int N, Np, C;
-    int ncb;                 // channel blocks per tile
+    int ncb;                 // channel blocks (units) per work item
+    int split_log2;          // a tile's channel blocks are spread over 2^split_log2 work items (split reduction)
     int ksteps_tap;          // 64-byte steps per filter tap in the packed weights
     int nsteps;              // steps per unit = KH * KW * CBS
     int plane_stride;        // bytes between the 16-channel planes of a patch buffer
-    int tiles_m, tiles_n;
+    int tiles_m, tiles_n;    // tiles_n counts work items: output-channel tiles x reduction splits
     PatchGeom g;
     TrimLuts luts;
 };
@@ -56,8 +57,10 @@ constexpr uint32_t kPatchInvalidOffset = 0x80000000u;   // beyond any buffer thi
 
 // TN output channels per workgroup, WGM x WGN wavefronts, AC 16-byte patch chunks per lane and
 // unit, CBS * 64 input channels per unit, WPC resident workgroups per CU the register budget allows.
-template <int TN, int WGM, int WGN, int AC, int CBS, int WPC>
+// SPLITK: the variant for split reductions (partial sums added to acc with atomics).
+template <int TN, int WGM, int WGN, int AC, int CBS, int WPC, bool SPLITK = false>
 struct PatchCfg {
+    static constexpr bool kSplitK = SPLITK;                  // results are added to acc with atomics (split reduction)
     static constexpr int kTM = kPatchTM, kTN = TN, kWGM = WGM, kWGN = WGN, kAC = AC, kCBS = CBS, kWgPerCu = WPC;
     static constexpr int kThreads = 64 * WGM * WGN;
     static constexpr int kWTM = kTM / WGM, kWTN = TN / WGN;
@@ -99,6 +102,7 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu) void conv_patch_kerne
     const int ntiles = p.tiles_m * p.tiles_n;
     const int grid = (int)gridDim.x;
     const int buf_bytes = PL * p.plane_stride;
+    const int split_mask = (1 << p.split_log2) - 1;
     const __amdgpu_buffer_rsrc_t xrsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.x), 0, (int)p.x_bytes, 0x00020000);
 
@@ -112,12 +116,14 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu) void conv_patch_kerne
     v4u a_reg[AC];                                // requested chunks (of the unit after next)
 
     // load cursor: the unit whose chunks are requested next; its tile's patch, uniform
-    int l_tile = (int)blockIdx.x, l_cb = 0;
+    int l_tile = (int)blockIdx.x, l_cb = 0, l_cb0 = 0;   // l_cb0: first channel block of the work item
     TilePatch lt;
     int stage_npix = 0;                           // patch size of the unit whose chunks are staged next
     auto load_tile_patch = [&]() __attribute__((always_inline)) {
         const bool live = l_tile < ntiles;
-        const TilePatch t = tile_patch(g, (live ? l_tile / p.tiles_n : 0) * kPatchTM);
+        const int tm = live ? l_tile / p.tiles_n : 0;
+        l_cb0 = ((l_tile - tm * p.tiles_n) & split_mask) * p.ncb;
+        const TilePatch t = tile_patch(g, tm * kPatchTM);
         lt.v0 = __builtin_amdgcn_readfirstlane(t.v0);
         lt.xlo = __builtin_amdgcn_readfirstlane(t.xlo);
         lt.pwt = __builtin_amdgcn_readfirstlane(t.pwt);
@@ -133,7 +139,7 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu) void conv_patch_kerne
     };
     auto load_chunk = [&](int i) __attribute__((always_inline)) {
         const int pix = my_pix + i * (NT / PL);
-        const int ch = l_cb * Cfg::kCB + my_c;
+        const int ch = (l_cb0 + l_cb) * Cfg::kCB + my_c;
         uint32_t off = patch_pixel_offset_u32(g, lt, pix, p.C, kPatchInvalidOffset);
         off = (ch < p.C) ? off : kPatchInvalidOffset;            // a tap's channel padding reads as zero
         off += (off != kPatchInvalidOffset) ? (uint32_t)ch : 0u;
@@ -202,8 +208,8 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu) void conv_patch_kerne
     const int grid_n = grid % p.tiles_n;
     int b_s = 0, b_cb = 0, b_tn = (int)blockIdx.x % p.tiles_n;
     auto next_b_offset = [&]() __attribute__((always_inline)) -> int {
-        const int kidx = (b_s / CBS) * p.ksteps_tap + b_cb * CBS + (b_s % CBS);
-        const int off = b_tn * TN * kChunk + kidx * 2 * w_half;
+        const int kidx = (b_s / CBS) * p.ksteps_tap + ((b_tn & split_mask) * p.ncb + b_cb) * CBS + (b_s % CBS);
+        const int off = (b_tn >> p.split_log2) * TN * kChunk + kidx * 2 * w_half;
         ++b_s;
         const bool ws = b_s == p.nsteps;
         b_s = ws ? 0 : b_s;
@@ -322,27 +328,42 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu) void conv_patch_kerne
             // Register v of fragment (i, j) is pixel 8*(v/4) + 4*lhi + v%4, channel l32: each store
             // instruction writes two full 128-byte runs of consecutive channels.
             const int64_t m0 = (int64_t)c_tm * kPatchTM;
-            const int n0 = c_tn * TN;
+            const int n0 = (c_tn >> p.split_log2) * TN;
+            const int corr_mul = (c_tn & split_mask) == 0 ? 128 : 0;       // only the first split adds the offset term
+            const float* scale_or_dummy = p.out ? p.scale : reinterpret_cast<const float*>(p.colsum);
+            // tiles that lie fully inside the M rows (all but the last) skip the per-row checks
+            auto store_tile = [&](auto full_) __attribute__((always_inline)) {
+                constexpr bool kFull = decltype(full_)::value;
 #pragma unroll
-            for (int j = 0; j < FN; ++j) {
-                const int n = n0 + wn * Cfg::kWTN + j * 32 + l32;
-                if (n >= p.N) continue;
-                const int32_t corr = 128 * p.colsum[n];
-                const float sc = p.out ? p.scale[n] : 0.0f;
+                for (int j = 0; j < FN; ++j) {
+                    const int n = n0 + wn * Cfg::kWTN + j * 32 + l32;
+                    if (n >= p.N) continue;
+                    // Both per-channel constants are loaded on every path (a load under a condition
+                    // makes the compiler put a full memory wait in front of every store below).
+                    int32_t corr = p.colsum[n] * corr_mul;
+                    float sc = scale_or_dummy[n];
+                    asm volatile("" : "+v"(corr), "+v"(sc));     // both loads have landed from here on
 #pragma unroll
-                for (int i = 0; i < FM; ++i) {
-                    const int64_t mb = m0 + wm * Cfg::kWTM + i * 32 + 4 * lhi;
+                    for (int i = 0; i < FM; ++i) {
+                        const int64_t mb = m0 + wm * Cfg::kWTM + i * 32 + 4 * lhi;
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int64_t m = mb + 8 * (v / 4) + (v % 4);
-                        if (m >= g.M) continue;
-                        const int32_t r = c[i][j][v] + corr;
-                        const int64_t o = m * p.N + n;
-                        if (p.acc) p.acc[o] = r;
-                        if (p.out) p.out[o] = __fmul_rn((float)r, sc);
+                        for (int v = 0; v < 16; ++v) {
+                            const int64_t m = mb + 8 * (v / 4) + (v % 4);
+                            if (!kFull && m >= g.M) continue;
+                            const int32_t r = c[i][j][v] + corr;
+                            const int64_t o = m * p.N + n;
+                            if constexpr (Cfg::kSplitK) {   // partial sum of a split reduction: int32 adds commute, the result is exact
+                                __hip_atomic_fetch_add(p.acc + o, r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            } else {
+                                if (p.acc) p.acc[o] = r;
+                                if (p.out) p.out[o] = __fmul_rn((float)r, sc);
+                            }
+                        }
                     }
                 }
-            }
+            };
+            if (m0 + kPatchTM <= g.M) store_tile(std::true_type{});
+            else store_tile(std::false_type{});
             zero_acc();
         }
         __syncthreads();
@@ -375,6 +396,7 @@ sparq_status launch_patch_cfg(const PatchParams& p, int npix_max, hipStream_t s)
     PatchParams q = p;
     q.plane_stride = patch_plane_stride(npix_max, Cfg::kPlanes);
     const int lds_bytes = 2 * Cfg::kPlanes * q.plane_stride + kChunk;     // two patch buffers + the dummy chunk
+    if ((p.split_log2 != 0) != Cfg::kSplitK) return SPARQ_EUNSUPPORTED;
     if (npix_max > Cfg::kMaxPix || lds_bytes > kLdsPerCu || q.nsteps < Cfg::kUnrolled ||
         ((q.nsteps - Cfg::kUnrolled) & 1))
         return SPARQ_EUNSUPPORTED;
@@ -387,7 +409,7 @@ sparq_status launch_patch_cfg(const PatchParams& p, int npix_max, hipStream_t s)
         lds_set = lds_bytes;
     }
     q.tiles_m = (p.g.M + kPatchTM - 1) / kPatchTM;
-    q.tiles_n = (p.N + Cfg::kTN - 1) / Cfg::kTN;
+    q.tiles_n = ((p.N + Cfg::kTN - 1) / Cfg::kTN) << p.split_log2;
     const int64_t tiles = (int64_t)q.tiles_m * q.tiles_n;
     if (tiles > 0x7FFFFFFF) return SPARQ_EUNSUPPORTED;
     int per_cu = kLdsPerCu / lds_bytes;
@@ -418,6 +440,12 @@ sparq_status launch_patch_kind(TrimKind kind, const PatchParams& p, int npix_max
 // One translation unit per tile shape instantiates every trim variant and exports a launcher.
 typedef sparq_status (*PatchLauncher)(TrimKind, const PatchParams&, int, hipStream_t);
 #define SPARQ_DECLARE_PATCH(name) sparq_status name(TrimKind kind, const PatchParams& p, int npix_max, hipStream_t s)
+SPARQ_DECLARE_PATCH(launch_patch_split_n128_a4c1);
+SPARQ_DECLARE_PATCH(launch_patch_split_n128_a8c1);
+SPARQ_DECLARE_PATCH(launch_patch_split_n128_a8c4);
+SPARQ_DECLARE_PATCH(launch_patch_n64_a12c1);
+SPARQ_DECLARE_PATCH(launch_patch_n128_a12c1);
+SPARQ_DECLARE_PATCH(launch_patch_n256_a12c1);
 SPARQ_DECLARE_PATCH(launch_patch_n64_a2c1);
 SPARQ_DECLARE_PATCH(launch_patch_n64_a4c1);
 SPARQ_DECLARE_PATCH(launch_patch_n64_a8c1);

@@ -1,0 +1,7 @@
+// Input-patch SPARQ convolution: 128 output pixels x 128 output channels per workgroup (2 x 2 wavefronts),
+// 12 patch chunks per lane and unit, 64 input channels per unit: all trim variants.
+#include "sparq_conv_patch_kernel.h"
+
+namespace sparq {
+SPARQ_DECLARE_PATCH(launch_patch_n128_a12c1) { return launch_patch_kind<PatchCfg<128, 2, 2, 12, 1, 2>>(kind, p, npix_max, s); }
+}  // namespace sparq

@@ -192,6 +192,24 @@ def test_conv_patch_channel_tiles(sq, oracle, monkeypatch, tn):
     check_layer(sq, oracle, S.ConvLayer("p_tn", 3, 14, 14, 128, 520, 3, 3, (1, 1), (1, 1)), S.Mode(4, S.OPT5, 1, 1), seed_cfg=9)
 
 
+@pytest.mark.parametrize("split", ["1", "2", "3"])
+@pytest.mark.parametrize("layer", [S.ConvLayer("split_3x3_c512", 3, 7, 7, 512, 130, 3, 3, (1, 1), (1, 1)),
+                                   S.ConvLayer("split_1x1_c2048", 1, 13, 11, 2048, 72)], ids=lambda l: l.name)
+def test_conv_split_reduction(sq, oracle, monkeypatch, layer, split):
+    """Small layers spread a tile's reduction over 2, 4 or 8 workgroups that add int32 partial sums
+    atomically: with the caller's acc as the sum buffer, and with the workspace when only out is asked for."""
+    monkeypatch.setenv("SPARQ_PATH", "patch")
+    monkeypatch.setenv("SPARQ_SPLIT", split)
+    mode = S.Mode(4, S.OPT5, 1, 1)
+    x, w, sc = S.gen_layer(9, layer)
+    ref_acc, ref_out = oracle.conv_gemm(x, w, layer.stride, layer.pad, scale=sc, **mode.kwargs())
+    acc, out = run_conv(sq, x, w, sc, layer, mode)
+    assert np.array_equal(acc, ref_acc)
+    assert np.all(np.abs(out.astype(np.float64) - ref_out) <= 1e-6 * np.abs(ref_out))
+    _, out_only = run_conv(sq, x, w, sc, layer, mode, want_acc=False)
+    assert np.array_equal(out_only, out)
+
+
 @pytest.mark.parametrize("mode", MODES_N4 + MODES_LOW + MODES_ODD, ids=lambda m: m.label + f"-{m.shift_mask:#x}")
 def test_conv_all_modes(sq, oracle, mode, path):
     check_layer(sq, oracle, S.ConvLayer("3x3_modes", 1, 14, 14, 64, 48, 3, 3, (1, 1), (1, 1), index=3), mode)
