@@ -5,8 +5,9 @@ One "step" is one pass of the fused path -- activation gather, vSPARQ/bSPARQ
 trim, int8 contraction, offset correction and per-channel dequantisation to
 fp32 -- over the workload's synthetic input, through the C ABI
 (``sparq_conv_gemm`` with ``out``).  The default workload is the large GEMM of
-the option sweep (M=65536, K=4608, N=512, 5opt, rounding, pairing on, 50 %
-zeros), the shape the int8-MFMA target is stated on.  The standalone trim and
+the option sweep (M=65536, K=4608 = 3x3x512, N=512, 5opt, rounding, pairing on,
+50 % zeros), the shape the int8-MFMA target is stated on, run as what it is: a
+3x3 convolution over 512 channels (64 images of 32x32), gathered implicitly.  The standalone trim and
 dequantisation kernels are timed next to it and reported in the same line.
 
 Prints ONE JSON line on stdout.
@@ -26,14 +27,24 @@ if ROOT not in sys.path:
 PEAK_INT8_TOPS = 5000.0     # MI355X dense int8 MFMA, published
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E, published
 
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of
+# this script (profiles/conv_gemm_cfg3_hbm_traffic.md).  FETCH_SIZE reads half the true figure on this
+# chip (calibrated on the trim kernel, which reads and writes exactly the tensor's size), WRITE_SIZE
+# reads true KiB; the figures below are already scaled.
+MEASURED_TRAFFIC = {
+    "cfg3-conv": {"fetch_bytes": 128_830_000, "write_bytes": 134_220_000},
+    "cfg3": {"fetch_bytes": 345_830_000, "write_bytes": 138_150_000},
+}
+
 
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--workload", default="cfg3",
-                    help="cfg3 (default: explicit GEMM A[M,K]) | cfg3-conv (same M,K,N as a 3x3x512 conv) | "
+    ap.add_argument("--workload", default="cfg3-conv",
+                    help="cfg3-conv (default: M=65536, K=3x3x512, N=512 as an implicit-GEMM 3x3 convolution) | "
+                         "cfg3 (the same M,K,N with a materialised A[M,K]) | "
                          "cfg0 | cfg1 | cfg2 | cfg4 | cfg4-2bit | cfg3-sweep (all 36 option points, table on stderr)")
     ap.add_argument("--mask", type=lambda s: int(s, 0), default=None, help="cfg3 only: shift mask override")
     ap.add_argument("--round", type=int, default=None, help="cfg3 only: rounding override")
@@ -217,9 +228,15 @@ def main():
     torch.cuda.synchronize()
     dom_ms = e0.elapsed_time(e1) / reps
     dom_tops = dom["layer"].ops / (dom_ms * 1e-3) / 1e12
+    tr = MEASURED_TRAFFIC.get(args.workload) if (args.rows == 65536 and args.mask is None and args.round is None
+                                                 and args.pair is None and args.zf is None) else None
+    x_b, w_b = dom["x"].numel(), dom["layer"].K * dom["layer"].N
     roofline = {"bound": "mfma", "achieved": round(dom_tops, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
-                "frac": round(dom_tops / PEAK_INT8_TOPS, 4), "traffic": None,
-                "kernel": "conv_gemm_kernel", "layer": dom["layer"].name, "ms_per_launch": round(dom_ms, 4),
+                "frac": round(dom_tops / PEAK_INT8_TOPS, 4),
+                "traffic": (tr["fetch_bytes"] + tr["write_bytes"]) if tr else None,
+                "traffic_detail": tr,
+                "algorithmic_bytes": x_b + w_b + 4 * dom["layer"].M * dom["layer"].N,
+                "kernel": sq.sparq_conv_plan(dom["d"], dom["m"]), "layer": dom["layer"].name, "ms_per_launch": round(dom_ms, 4),
                 "ops_per_launch": dom["layer"].ops}
 
     # ---- standalone trim and dequant kernels (HBM-bound), on the dominant layer's tensors ----
@@ -264,12 +281,13 @@ def main():
             print(f"{L.name:28s} {L.M:8d} {L.K:6d} {L.N:5d} {L.repeat:3d} {ms:9.4f} {L.ops / ms / 1e9:8.1f}",
                   file=sys.stderr)
 
-    # ---- secondary figures of the default run: the same GEMM as an implicit 3x3 convolution, and the
-    #      ResNet-18 layer table (small layers that do not fill the chip) ----
+    # ---- secondary figures of the default run: the same GEMM with a materialised A[M,K] (no reuse
+    #      between filter taps), the ResNet-18 layer table (small layers that do not fill the chip)
+    #      and the Inception-shaped table ----
     also = None
-    if args.workload == "cfg3" and not args.no_extra and args.rows == 65536:
+    if args.workload == "cfg3-conv" and not args.no_extra and args.rows == 65536:
         also = []
-        for wl in ("cfg3-conv", "cfg1"):
+        for wl in ("cfg3", "cfg1", "cfg4"):
             a2 = argparse.Namespace(**{**vars(args), "workload": wl})
             c2, l2, n2 = build_workload(a2)
             it2 = prepare(sq, S, torch, dev, c2, l2)

@@ -102,6 +102,13 @@ sparq_status sparq_pack_weights(const int8_t *w, const sparq_conv_desc *desc,
  * calls that share one workspace must not overlap. */
 size_t sparq_workspace_bytes(const sparq_conv_desc *desc, const sparq_mode *mode);
 
+/* Which kernel and tiling sparq_conv_gemm would use for this descriptor and mode
+ * on the current device, as a short human-readable line (for logs and profiles;
+ * the wording is not an interface).  text receives at most text_bytes bytes
+ * including the terminator. */
+sparq_status sparq_conv_plan(const sparq_conv_desc *desc, const sparq_mode *mode,
+                             char *text, size_t text_bytes);
+
 /* Eq. 1 over trimmed activations as an implicit GEMM:
  *   acc[m][n] = sum_{kh,kw,c} T(x)[b, oy*stride_h - pad_h + kh, ox*stride_w - pad_w + kw, c] * w[n][kh][kw][c]
  * (zero outside the image), exact in int32, and optionally

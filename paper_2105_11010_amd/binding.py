@@ -50,6 +50,8 @@ def _load() -> ctypes.CDLL:
     L.sparq_pack_weights.restype = ctypes.c_int
     L.sparq_workspace_bytes.argtypes = [pd, pm]
     L.sparq_workspace_bytes.restype = sz
+    L.sparq_conv_plan.argtypes = [pd, pm, ctypes.c_char_p, sz]
+    L.sparq_conv_plan.restype = ctypes.c_int
     L.sparq_conv_gemm.argtypes = [vp, vp, pd, pm, vp, vp, vp, vp, sz, vp]
     L.sparq_conv_gemm.restype = ctypes.c_int
     L.sparq_dequant.argtypes = [vp, vp, vp, i64, i32, vp]
@@ -113,6 +115,13 @@ def sparq_packed_bytes(d: SparqConvDesc) -> int:
 
 def sparq_workspace_bytes(d: SparqConvDesc, m: SparqMode) -> int:
     return int(lib.sparq_workspace_bytes(ctypes.byref(d), ctypes.byref(m)))
+
+
+def sparq_conv_plan(d: SparqConvDesc, m: SparqMode) -> str:
+    """Which kernel and tiling sparq_conv_gemm would use (a line of text for logs)."""
+    buf = ctypes.create_string_buffer(256)
+    _check(lib.sparq_conv_plan(ctypes.byref(d), ctypes.byref(m), buf, len(buf)), "sparq_conv_plan")
+    return buf.value.decode()
 
 
 def sparq_pack_weights(w: torch.Tensor, d: SparqConvDesc, packed: torch.Tensor) -> None:

@@ -3,6 +3,7 @@
 #include "sparq_conv_gemm_kernel.h"
 #include "sparq_conv_patch_kernel.h"
 
+#include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
 
@@ -202,6 +203,23 @@ extern "C" size_t sparq_workspace_bytes(const sparq_conv_desc* desc, const sparq
     if (!conv_geom(desc, &g) || !mode_valid(mode)) return 0;
     const ConvPlan pl = make_plan(g);
     return pl.pad_bytes + pl.split_bytes;
+}
+
+extern "C" sparq_status sparq_conv_plan(const sparq_conv_desc* desc, const sparq_mode* mode, char* text, size_t text_bytes) {
+    ConvGeom g;
+    if (!text || text_bytes == 0 || !conv_geom(desc, &g) || !mode_valid(mode)) return SPARQ_EINVAL;
+    const ConvPlan pl = make_plan(g);
+    if (pl.patch) {
+        snprintf(text, text_bytes, "conv_patch_kernel tile=128x%d chunks=%d unit_channels=%d split=%d patch_pixels=%d%s",
+                 pl.variant->tn, pl.ac, 64 * pl.cbs, 1 << pl.split_log2, pl.npix, pl.pad_bytes ? " padded_copy" : "");
+    } else {
+        const char* name = "?";
+        const TileLauncher fn = pick_tile(g);
+        for (const TileEntry& t : kTiles)
+            if (t.fn == fn) name = t.name;
+        snprintf(text, text_bytes, "conv_gemm_kernel tile=%s%s", name, pl.pad_bytes ? " padded_copy" : "");
+    }
+    return SPARQ_OK;
 }
 
 extern "C" sparq_status sparq_conv_gemm(const uint8_t* x, const void* packed_w, const sparq_conv_desc* desc,
