@@ -1,7 +1,8 @@
 """GPU parity at the benchmark's full sizes: every layer of the five workload tables runs through
 the C ABI exactly as bench.py launches it (full tensors, fused dequantisation); the CPU oracle then
 recomputes a sample of output rows one by one -- first and last tile, image borders, random interior
-rows -- and those must match bit-exactly (int32) and to 1e-6 relative (fp32)."""
+rows; 4096 and more rows on the largest layers -- and those must match bit-exactly (int32) and to
+1e-6 relative (fp32)."""
 from dataclasses import replace
 
 import numpy as np
@@ -65,6 +66,7 @@ def _check_one(sq, oracle, layer, data, n):
     torch.cuda.synchronize()
     del acc, out, deq, xd
     ref_acc, ref_out = oracle.conv_gemm(x, w, layer.stride, layer.pad, scale=sc, rows=rows, **layer.mode.kwargs())
+    assert int(got_acc.astype(np.int64).sum()) == int(ref_acc.astype(np.int64).sum()), f"{layer.name}: checksum of sampled rows"
     assert np.array_equal(got_acc, ref_acc), f"{layer.name} {layer.mode.label}: int32 mismatch on sampled rows"
     assert np.all(np.abs(got_out.astype(np.float64) - ref_out) <= 1e-6 * np.abs(ref_out)), f"{layer.name}: fp32 off"
 
@@ -72,7 +74,7 @@ def _check_one(sq, oracle, layer, data, n):
 # ---- config 1: ResNet-18, batch 32, 3opt floor (first conv plain 8-bit) --------------------------
 @pytest.mark.parametrize("layer", S.config1(), ids=lambda l: l.name)
 def test_config1_resnet18(sq, oracle, layer):
-    check_sampled(sq, oracle, 1, layer)
+    check_sampled(sq, oracle, 1, layer, n=1024)
 
 
 # ---- config 2: ResNet-50, batch 256, 5opt round ---------------------------------------------------
@@ -84,12 +86,12 @@ _C2_FULL = {"conv1_7x7s2", "s1b1_1x1_64_256", "s1bx_1x1_256_64", "s2b1_3x3s2_128
 @pytest.mark.parametrize("layer", [l for l in _C2 if l.name in _C2_FULL], ids=lambda l: l.name)
 def test_config2_resnet50_full_batch(sq, oracle, layer):
     """The largest tensors of the stack at batch 256 (input up to 205 MB, fp32 output up to 822 MB)."""
-    check_sampled(sq, oracle, 2, layer, n=96)
+    check_sampled(sq, oracle, 2, layer, n=4096)
 
 
 @pytest.mark.parametrize("layer", [replace(l, B=8) for l in _C2 if l.name not in _C2_FULL], ids=lambda l: l.name)
 def test_config2_resnet50_other_layers_small_batch(sq, oracle, layer):
-    check_sampled(sq, oracle, 2, layer, n=96)
+    check_sampled(sq, oracle, 2, layer, n=512)
 
 
 # ---- config 3: the option sweep on M=65536, K=4608, N=512 ------------------------------------------
@@ -97,13 +99,13 @@ def test_config2_resnet50_other_layers_small_batch(sq, oracle, layer):
                                       (0.2, [S.Mode(4, S.OPT3, 0, 1)]),
                                       (0.8, [S.Mode(4, S.OPT2, 1, 0)])], ids=["zf0.5", "zf0.2", "zf0.8"])
 def test_config3_full_size(sq, oracle, zf, modes):
-    check_sampled(sq, oracle, 3, replace(S.config3_layer(), zf=zf), n=64, modes=modes)
+    check_sampled(sq, oracle, 3, replace(S.config3_layer(), zf=zf), n=4096, modes=modes)
 
 
 def test_config3_full_size_as_convolution(sq, oracle):
     """The same M, K, N as a 3x3 convolution over 512 channels (the form bench.py also times)."""
     layer = replace(S.config3_layer(), name="conv3x3_512_512_32x32", B=64, H=32, W=32, C=512, KH=3, KW=3, pad=(1, 1))
-    check_sampled(sq, oracle, 3, layer, n=64)
+    check_sampled(sq, oracle, 3, layer, n=4096)
 
 
 @pytest.mark.parametrize("mode,zf", S.config3_sweep(), ids=lambda v: v.label if isinstance(v, S.Mode) else f"zf{v}")
@@ -116,4 +118,4 @@ def test_config3_sweep_all_36_points_small_m(sq, oracle, mode, zf):
 def test_config4_inception_4bit_and_2bit(sq, oracle, layer):
     """Both passes of the workload on the same tensors: 4-bit 5opt rounding, then the 2-bit window
     with 7 shifts where a zero partner grants 4 bits."""
-    check_sampled(sq, oracle, 4, layer, n=96, modes=[layer.mode, S.Mode(2, S.OPT7_2B, 1, 1)])
+    check_sampled(sq, oracle, 4, layer, n=512, modes=[layer.mode, S.Mode(2, S.OPT7_2B, 1, 1)])
