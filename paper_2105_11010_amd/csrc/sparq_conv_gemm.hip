@@ -36,16 +36,26 @@ TileLauncher pick_tile(const ConvGeom& g) {
 }
 
 // ---- input-patch kernel: eligibility and variant choice --------------------------------------
-struct PatchVariant { int tn, ac, cbs; PatchLauncher fn; PatchLauncher fn_split; };   // fn_split: null if not built
+struct PatchVariant { int tn, ac, cbs; PatchLauncher fn; PatchLauncher fn_split; PatchLauncher fn_ws; };   // fn_split / fn_ws: null if not built
 const PatchVariant kPatchVariants[] = {
-    {64, 12, 1, launch_patch_n64_a12c1}, {128, 12, 1, launch_patch_n128_a12c1}, {256, 12, 1, launch_patch_n256_a12c1},
-    {64, 2, 1, launch_patch_n64_a2c1},   {64, 4, 1, launch_patch_n64_a4c1},   {64, 8, 1, launch_patch_n64_a8c1},
-    {64, 4, 2, launch_patch_n64_a4c2},   {64, 8, 4, launch_patch_n64_a8c4},
-    {128, 2, 1, launch_patch_n128_a2c1}, {128, 4, 1, launch_patch_n128_a4c1, launch_patch_split_n128_a4c1},
-    {128, 8, 1, launch_patch_n128_a8c1, launch_patch_split_n128_a8c1},
-    {128, 4, 2, launch_patch_n128_a4c2}, {128, 8, 4, launch_patch_n128_a8c4, launch_patch_split_n128_a8c4},
-    {256, 2, 1, launch_patch_n256_a2c1}, {256, 4, 1, launch_patch_n256_a4c1}, {256, 8, 1, launch_patch_n256_a8c1},
-    {256, 4, 2, launch_patch_n256_a4c2}, {256, 8, 4, launch_patch_n256_a8c4},
+    {64, 2, 1, launch_patch_n64_a2c1, nullptr, nullptr},
+    {64, 4, 1, launch_patch_n64_a4c1, nullptr, nullptr},
+    {64, 8, 1, launch_patch_n64_a8c1, nullptr, nullptr},
+    {64, 12, 1, launch_patch_n64_a12c1, nullptr, nullptr},
+    {64, 4, 2, launch_patch_n64_a4c2, nullptr, nullptr},
+    {64, 8, 4, launch_patch_n64_a8c4, nullptr, nullptr},
+    {128, 2, 1, launch_patch_n128_a2c1, nullptr, launch_patch_ws_n128_a2c1},
+    {128, 4, 1, launch_patch_n128_a4c1, launch_patch_split_n128_a4c1, launch_patch_ws_n128_a4c1},
+    {128, 8, 1, launch_patch_n128_a8c1, launch_patch_split_n128_a8c1, launch_patch_ws_n128_a8c1},
+    {128, 12, 1, launch_patch_n128_a12c1, nullptr, launch_patch_ws_n128_a12c1},
+    {128, 4, 2, launch_patch_n128_a4c2, nullptr, launch_patch_ws_n128_a4c2},
+    {128, 8, 4, launch_patch_n128_a8c4, launch_patch_split_n128_a8c4, launch_patch_ws_n128_a8c4},
+    {256, 2, 1, launch_patch_n256_a2c1, nullptr, launch_patch_ws_n256_a2c1},
+    {256, 4, 1, launch_patch_n256_a4c1, nullptr, launch_patch_ws_n256_a4c1},
+    {256, 8, 1, launch_patch_n256_a8c1, nullptr, launch_patch_ws_n256_a8c1},
+    {256, 12, 1, launch_patch_n256_a12c1, nullptr, launch_patch_ws_n256_a12c1},
+    {256, 4, 2, launch_patch_n256_a4c2, nullptr, launch_patch_ws_n256_a4c2},
+    {256, 8, 4, launch_patch_n256_a8c4, nullptr, launch_patch_ws_n256_a8c4},
 };
 
 // Largest patch (in pixels) any tile of this geometry needs.  Tile positions repeat relative to the
@@ -116,26 +126,36 @@ bool plan_patch(const ConvGeom& g, PatchGeom* pg, int* npix, int* ac, int* cbs) 
     return false;
 }
 
-// Output-channel tile of the patch kernel: 64 for narrow layers; otherwise 128 (two workgroups per
-// CU hide each other's latencies), 256 only for long reductions over a multiple of 256 channels
-// with enough tiles to fill the chip.  SPARQ_PATCH_TN=<n> (a tuning knob) forces one.
-const PatchVariant* pick_patch(const ConvGeom& g, int ac, int cbs, int npix, bool forced) {
+// Output-channel tile and form of the patch kernel.
+//   64 for narrow layers; otherwise 128, two workgroups per CU that hide each other's latencies;
+//   256 (one workgroup per CU, wave-specialised: 4 matrix + 4 staging wavefronts) for long reductions over a
+//   multiple of 256 channels with tiles for at least half the chip; 256 in the plain form for patches so
+//   large that LDS holds one workgroup per CU anyway (strided 3x3 layers on large images) when the layer is
+//   wide and fills the chip.  A 128 tile whose layer has no more tiles than CUs runs alone on its CU: it
+//   takes the wave-specialised form as well (unless its reduction is split).
+// SPARQ_PATCH_TN=<n> and SPARQ_PATCH_WS=0|1 (tuning knobs) force the choice.
+const PatchVariant* pick_patch(const ConvGeom& g, int ac, int cbs, int npix, bool forced, bool* ws) {
     const int64_t tiles_m = (g.M + kPatchTM - 1) / kPatchTM;
+    const int cus = device_cu_count();
     int tn = g.N <= 64 ? 64 : 128;
-    if (g.N >= 512 && g.N % 256 == 0 && g.K >= 2048 && tiles_m * (g.N / 256) >= device_cu_count()) tn = 256;
-    // A patch so large that only one workgroup fits a CU's LDS (strided 3x3 layers on large
-    // images): the two-workgroup tiles lose their point; wide layers take the 256 tile, narrow
-    // ones are left to the gather kernel.
+    *ws = false;
+    const bool small_patch = ac <= 8;              // staging a larger patch keeps four wavefronts busier than the matrix work
+    if (g.N >= 256 && g.N % 256 == 0 && g.K >= 2048 && tiles_m * (g.N / 256) * 2 >= cus) { tn = 256; *ws = small_patch; }
     if (2 * 4 * cbs * patch_plane_stride(npix, 4 * cbs) > kLdsPerCu / 2) {
-        if (g.N >= 256) tn = 256;
-        else if (!forced) return nullptr;
+        if (g.N >= 256 && tiles_m * ((g.N + 255) / 256) >= cus) { tn = 256; *ws = false; }
+        else if (g.N < 256 && tiles_m * ((g.N + 127) / 128) >= cus && !forced) return nullptr;   // narrow: gather kernel
     }
+    if (tn == 128 && tiles_m * ((g.N + 127) / 128) <= cus) *ws = small_patch;
     if (const char* e = getenv("SPARQ_PATCH_TN")) {
         const int v = atoi(e);
         if ((v == 64 || v == 128 || v == 256) && tile_fits(v, g)) tn = v;
     }
+    if (const char* e = getenv("SPARQ_PATCH_WS")) *ws = atoi(e) != 0;
     for (const PatchVariant& v : kPatchVariants)
-        if (v.tn == tn && v.ac == ac && v.cbs == cbs) return &v;
+        if (v.tn == tn && v.ac == ac && v.cbs == cbs) {
+            if (!v.fn_ws) *ws = false;
+            return &v;
+        }
     return nullptr;
 }
 
@@ -174,6 +194,7 @@ struct ConvPlan {
     const PatchVariant* variant = nullptr;
     PatchGeom pg{};
     int npix = 0, ac = 0, cbs = 0, split_log2 = 0;
+    bool ws = false;            // wave-specialised form of the patch kernel
     size_t pad_bytes = 0;       // channel-padded copy of x (channel counts that are not a multiple of 16)
     size_t split_bytes = 0;     // int32 partial sums of a split reduction when the caller passes no acc
 };
@@ -186,7 +207,7 @@ ConvPlan make_plan(const ConvGeom& g) {
     ConvGeom gk = g;
     gk.C = gk.Cp;                                                // what the kernel sees after the padding pre-pass
     if (!force_gather && (force_patch || !prefer_gather(g)) && plan_patch(gk, &pl.pg, &pl.npix, &pl.ac, &pl.cbs)) {
-        pl.variant = pick_patch(g, pl.ac, pl.cbs, pl.npix, force_patch);
+        pl.variant = pick_patch(g, pl.ac, pl.cbs, pl.npix, force_patch, &pl.ws);
         if (pl.variant) {
             pl.patch = true;
             pl.split_log2 = pick_split_log2(g, *pl.variant, g.Cq / kStepK / pl.cbs);
@@ -210,8 +231,9 @@ extern "C" sparq_status sparq_conv_plan(const sparq_conv_desc* desc, const sparq
     if (!text || text_bytes == 0 || !conv_geom(desc, &g) || !mode_valid(mode)) return SPARQ_EINVAL;
     const ConvPlan pl = make_plan(g);
     if (pl.patch) {
-        snprintf(text, text_bytes, "conv_patch_kernel tile=128x%d chunks=%d unit_channels=%d split=%d patch_pixels=%d%s",
-                 pl.variant->tn, pl.ac, 64 * pl.cbs, 1 << pl.split_log2, pl.npix, pl.pad_bytes ? " padded_copy" : "");
+        snprintf(text, text_bytes, "conv_patch_kernel tile=128x%d chunks=%d unit_channels=%d split=%d patch_pixels=%d%s%s",
+                 pl.variant->tn, pl.ac, 64 * pl.cbs, 1 << pl.split_log2, pl.npix,
+                 (pl.ws && !pl.split_log2) ? " wave_specialised" : "", pl.pad_bytes ? " padded_copy" : "");
     } else {
         const char* name = "?";
         const TileLauncher fn = pick_tile(g);
@@ -285,7 +307,8 @@ extern "C" sparq_status sparq_conv_gemm(const uint8_t* x, const void* packed_w, 
             if (st == SPARQ_OK && out) st = sparq_dequant(sum, scale, out, g.M, g.N, stream);
             if (st != SPARQ_EUNSUPPORTED) return st;
         } else {
-            const sparq_status st = pl.variant->fn(kind, q, pl.npix, s);
+            const PatchLauncher fn = pl.ws ? pl.variant->fn_ws : pl.variant->fn;
+            const sparq_status st = fn(kind, q, pl.npix, s);
             if (st != SPARQ_EUNSUPPORTED) return st;
         }
     }

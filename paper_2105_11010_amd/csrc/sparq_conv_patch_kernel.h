@@ -58,22 +58,29 @@ constexpr uint32_t kPatchInvalidOffset = 0x80000000u;   // beyond any buffer thi
 // TN output channels per workgroup, WGM x WGN wavefronts, AC 16-byte patch chunks per lane and
 // unit, CBS * 64 input channels per unit, WPC resident workgroups per CU the register budget allows.
 // SPLITK: the variant for split reductions (partial sums added to acc with atomics).
-template <int TN, int WGM, int WGN, int AC, int CBS, int WPC, bool SPLITK = false>
+// WS: wave-specialised variant -- wavefronts 4..7 load, trim and stage the patches, wavefronts 0..3 only read
+// fragments and weights and multiply.  A wavefront's loads return in order, so in the plain variant a weight wait
+// also waits for every older (slow, HBM) activation load; with separate wavefronts it does not, and the trim
+// arithmetic issues from other wavefronts while the matrix instructions run.
+template <int TN, int WGM, int WGN, int AC, int CBS, int WPC, bool SPLITK = false, bool WS = false>
 struct PatchCfg {
+    static constexpr bool kWaveSpecialised = WS;            // four more wavefronts do the loading, trimming and staging
     static constexpr bool kSplitK = SPLITK;                  // results are added to acc with atomics (split reduction)
     static constexpr int kTM = kPatchTM, kTN = TN, kWGM = WGM, kWGN = WGN, kAC = AC, kCBS = CBS, kWgPerCu = WPC;
-    static constexpr int kThreads = 64 * WGM * WGN;
+    static constexpr int kMathThreads = 64 * WGM * WGN;
+    static constexpr int kStageThreads = 256;
+    static constexpr int kThreads = kMathThreads + (WS ? kStageThreads : 0);
     static constexpr int kWTM = kTM / WGM, kWTN = TN / WGN;
     static constexpr int kFM = kWTM / 32, kFN = kWTN / 32;
     static constexpr int kPlanes = 4 * CBS;                  // 16-channel planes per patch buffer
     static constexpr int kCB = 64 * CBS;
-    static constexpr int kAS = (AC + 1) / 2;                 // steps of a unit that also stage and load patch chunks
-    static constexpr int kMaxPix = AC * kThreads / kPlanes;  // patch pixels one unit can stage
+    static constexpr int kAS = WS ? 0 : (AC + 1) / 2;        // steps of a unit that also stage and load patch chunks
+    static constexpr int kMaxPix = AC * kStageThreads / kPlanes;   // patch pixels one unit can stage
     // 64-channel units cover multi-tap filters with an odd number of taps (1x1 included); wider
     // units are for 1x1 filters only, where steps per unit = CBS is even
     static constexpr bool kOddSteps = CBS == 1;
     static constexpr int kUnrolled = kAS + (((kAS & 1) != (kOddSteps ? 1 : 0)) ? 1 : 0);
-    static_assert(kThreads == 256, "patch staging assumes 256 lanes");
+    static_assert(kMathThreads == 256, "four matrix wavefronts");
     static_assert(kTM % (32 * WGM) == 0 && TN % (32 * WGN) == 0, "tile must split into 32x32 fragments");
     static_assert(CBS == 1 || CBS == 2 || CBS == 4, "channel block");
     static_assert(AC >= 2 && AC % 2 == 0, "chunks per lane");
@@ -88,14 +95,17 @@ inline int patch_plane_stride(int npix_max, int planes) {
 template <int V> using int_c = std::integral_constant<int, V>;
 
 template <class Cfg, int KIND>
-__global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu) void conv_patch_kernel(const PatchParams p) {
-    constexpr int NT = Cfg::kThreads, FM = Cfg::kFM, FN = Cfg::kFN, AC = Cfg::kAC, CBS = Cfg::kCBS, AS = Cfg::kAS;
+__global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256) void conv_patch_kernel(const PatchParams p) {
+    constexpr bool WS = Cfg::kWaveSpecialised;
+    constexpr int NT = Cfg::kStageThreads, FM = Cfg::kFM, FN = Cfg::kFN, AC = Cfg::kAC, CBS = Cfg::kCBS, AS = Cfg::kAS;
     constexpr int PL = Cfg::kPlanes, TN = Cfg::kTN;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];     // [2][PL][plane_stride]
 
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave_all = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    const bool producer = WS && wave_all >= 4;            // uniform per wavefront
+    const int wave = wave_all & 3;
+    const int tid = wave * 64 + lane;                     // index inside the role's 256 lanes
     const int wm = wave % Cfg::kWGM, wn = wave / Cfg::kWGM;
     const int l32 = lane & 31, lhi = lane >> 5;
     const PatchGeom& g = p.g;
@@ -240,9 +250,11 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu) void conv_patch_kerne
 
     // ---- prologue: unit 0 staged, unit 1 requested, two weight steps requested ----
     load_tile_patch();
+    if (!WS || producer) {
 #pragma unroll
-    for (int i = 0; i < AC; ++i) load_chunk(i);
-    {
+        for (int i = 0; i < AC; ++i) load_chunk(i);
+    }
+    if (!producer) {
         const int w0 = next_b_offset();
         load_b(b_reg[0][0], w0, 0);
         load_b(b_reg[0][1], w0, 1);
@@ -251,12 +263,16 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu) void conv_patch_kerne
         load_b(b_reg[1][1], w1, 1);
     }
     stage_npix = lt.npix;
+    if (!WS || producer) {
 #pragma unroll
-    for (int i = 0; i < AC; ++i) stage_chunk(i, lds);
+        for (int i = 0; i < AC; ++i) stage_chunk(i, lds);
+    }
     advance_load_cursor();
     stage_npix = lt.npix;                         // unit 1 is staged while unit 0 is multiplied
+    if (!WS || producer) {
 #pragma unroll
-    for (int i = 0; i < AC; ++i) load_chunk(i);
+        for (int i = 0; i < AC; ++i) load_chunk(i);
+    }
     advance_load_cursor();
     setup_compute_tile();
     zero_acc();
@@ -302,6 +318,15 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu) void conv_patch_kerne
     constexpr int U0 = Cfg::kUnrolled;
     auto run_unit = [&](auto P_, const uint8_t* rbuf, uint8_t* sbuf) __attribute__((always_inline)) {
         constexpr int P = decltype(P_)::value;
+        if (producer) {
+            // staging wavefronts: trim and write the next unit's chunks, request those of the unit after it
+#pragma unroll
+            for (int i = 0; i < AC; ++i) {
+                stage_chunk(i, sbuf);
+                load_chunk(i);
+            }
+            return;
+        }
         f_j = f_kw = f_kh = f_off = 0;
         load_frags(a_frag[P], rbuf);
         auto head = [&](auto self, auto s_) __attribute__((always_inline)) {
@@ -323,7 +348,7 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu) void conv_patch_kerne
     int ubuf = 0;
     auto boundary = [&]() __attribute__((always_inline)) {
         ubuf ^= 1;
-        if (c_cb == p.ncb - 1) {
+        if (!producer && c_cb == p.ncb - 1) {
             // ---- epilogue: undo the -128 offset, store int32 and/or dequantised fp32 ----
             // Register v of fragment (i, j) is pixel 8*(v/4) + 4*lhi + v%4, channel l32: each store
             // instruction writes two full 128-byte runs of consecutive channels.
@@ -440,6 +465,18 @@ sparq_status launch_patch_kind(TrimKind kind, const PatchParams& p, int npix_max
 // One translation unit per tile shape instantiates every trim variant and exports a launcher.
 typedef sparq_status (*PatchLauncher)(TrimKind, const PatchParams&, int, hipStream_t);
 #define SPARQ_DECLARE_PATCH(name) sparq_status name(TrimKind kind, const PatchParams& p, int npix_max, hipStream_t s)
+SPARQ_DECLARE_PATCH(launch_patch_ws_n128_a2c1);
+SPARQ_DECLARE_PATCH(launch_patch_ws_n128_a4c1);
+SPARQ_DECLARE_PATCH(launch_patch_ws_n128_a8c1);
+SPARQ_DECLARE_PATCH(launch_patch_ws_n128_a12c1);
+SPARQ_DECLARE_PATCH(launch_patch_ws_n128_a4c2);
+SPARQ_DECLARE_PATCH(launch_patch_ws_n128_a8c4);
+SPARQ_DECLARE_PATCH(launch_patch_ws_n256_a2c1);
+SPARQ_DECLARE_PATCH(launch_patch_ws_n256_a4c1);
+SPARQ_DECLARE_PATCH(launch_patch_ws_n256_a8c1);
+SPARQ_DECLARE_PATCH(launch_patch_ws_n256_a12c1);
+SPARQ_DECLARE_PATCH(launch_patch_ws_n256_a4c2);
+SPARQ_DECLARE_PATCH(launch_patch_ws_n256_a8c4);
 SPARQ_DECLARE_PATCH(launch_patch_split_n128_a4c1);
 SPARQ_DECLARE_PATCH(launch_patch_split_n128_a8c1);
 SPARQ_DECLARE_PATCH(launch_patch_split_n128_a8c4);

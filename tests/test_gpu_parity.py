@@ -140,13 +140,16 @@ SHAPES = [
 # The library holds two convolution kernels (an im2col-gather form and an input-patch form) and
 # picks one per layer; SPARQ_PATH forces either where the layer is eligible, so both are compared
 # with the oracle on every shape.
-@pytest.fixture(params=["auto", "gather", "patch"])
+@pytest.fixture(params=["auto", "gather", "patch", "patch-ws"])
 def path(request, monkeypatch):
-    monkeypatch.delenv("SPARQ_PATH", raising=False)
-    monkeypatch.delenv("SPARQ_PATCH_TN", raising=False)
-    monkeypatch.delenv("SPARQ_TILE", raising=False)
-    if request.param != "auto":
+    for k in ("SPARQ_PATH", "SPARQ_PATCH_TN", "SPARQ_TILE", "SPARQ_PATCH_WS", "SPARQ_SPLIT"):
+        monkeypatch.delenv(k, raising=False)
+    if request.param == "patch-ws":      # the wave-specialised form of the patch kernel
+        monkeypatch.setenv("SPARQ_PATH", "patch")
+        monkeypatch.setenv("SPARQ_PATCH_WS", "1")
+    elif request.param != "auto":
         monkeypatch.setenv("SPARQ_PATH", request.param)
+        monkeypatch.setenv("SPARQ_PATCH_WS", "0")
     return request.param
 
 
