@@ -76,7 +76,17 @@ struct ConvGeom {
     size_t w_off;    // byte offset of the weight tiles inside the packed buffer
     size_t packed_bytes;
     size_t x_bytes;
+    // Pixel folding for layers with at most 4 channels (a network's first convolution): four
+    // neighbouring pixels of a row, each padded to 4 channels, become one 16-channel "super-pixel".
+    // Output columns split into fold_p = 4 / stride_w classes by their position inside a super-pixel;
+    // class p of output channel n becomes output channel p*N + n of a stride-1 convolution over
+    // super-pixels with fold_kw taps per row -- and [M/fold_p][fold_p*N] is the same memory as [M][N].
+    bool fold;
+    int fold_p, fold_kw, fold_kw_min, fold_pw;
 };
+
+inline int floor_div(int a, int b) { return a >= 0 ? a / b : -((-a + b - 1) / b); }
+
 
 inline bool conv_geom(const sparq_conv_desc* d, ConvGeom* g) {
     if (!d) return false;
@@ -103,7 +113,39 @@ inline bool conv_geom(const sparq_conv_desc* d, ConvGeom* g) {
     g->w_off = (size_t)round_up((int64_t)g->Np * 4, 256);
     g->packed_bytes = g->w_off + (size_t)g->Kp * (size_t)g->Np;
     g->x_bytes = (size_t)d->B * d->H * d->W * (size_t)d->C;
+    g->fold = false;
+    g->fold_p = 1; g->fold_kw = d->KW; g->fold_kw_min = 0; g->fold_pw = d->pad_w;
+    if (d->C <= 4 && d->W % 4 == 0 && 4 % d->stride_w == 0 && d->KH * d->KW > 1) {
+        const int P = 4 / d->stride_w;
+        const int kw_min = floor_div(-d->pad_w, 4);
+        const int kw_max = floor_div(d->stride_w * (P - 1) - d->pad_w + d->KW - 1, 4);
+        const int KWf = kw_max - kw_min + 1, pwf = -kw_min;
+        if (g->Wo % P == 0 && d->W / 4 + 2 * pwf - KWf + 1 == g->Wo / P) {
+            g->fold = true;
+            g->fold_p = P; g->fold_kw = KWf; g->fold_kw_min = kw_min; g->fold_pw = pwf;
+            // sizes of the packed weights of the folded problem: 16 channels per tap, fold_p * N outputs
+            const int64_t Kf = (int64_t)d->KH * KWf * 16;
+            g->Kp = (int)round_up(Kf, kStepK);
+            g->Np = (int)round_up((int64_t)P * d->N, kPadN);
+            g->w_off = (size_t)round_up((int64_t)g->Np * 4, 256);
+            g->packed_bytes = g->w_off + (size_t)g->Kp * (size_t)g->Np;
+        }
+    }
     return true;
+}
+
+// The convolution the kernels see when `g` is folded: super-pixels of 16 channels, stride 1 along W.
+inline ConvGeom folded_view(const ConvGeom& g) {
+    ConvGeom f = g;
+    f.W = g.W / 4; f.C = 16; f.Cp = 16; f.Cq = 16;
+    f.N = g.fold_p * g.N;
+    f.KW = g.fold_kw; f.sw = 1; f.pw = g.fold_pw;
+    f.Wo = g.Wo / g.fold_p;
+    f.M = g.M / g.fold_p;
+    f.Kk = g.KH * g.fold_kw * 16;
+    f.x_bytes = (size_t)g.B * g.H * g.W * 4;
+    f.fold = false;
+    return f;
 }
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }

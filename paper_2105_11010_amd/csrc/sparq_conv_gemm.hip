@@ -201,6 +201,10 @@ struct ConvPlan {
 
 ConvPlan make_plan(const ConvGeom& g) {
     ConvPlan pl;
+    if (g.fold) {               // at most 4 channels: 4-channel padded copy, pixel-folded, gather kernel
+        pl.pad_bytes = (size_t)round_up((int64_t)g.B * g.H * g.W * 4, 256);
+        return pl;
+    }
     if (g.Cp != g.C) pl.pad_bytes = (size_t)round_up((int64_t)g.B * g.H * g.W * g.Cp, 256);
     const char* path = getenv("SPARQ_PATH");
     const bool force_gather = path && !strcmp(path, "gather"), force_patch = path && !strcmp(path, "patch");
@@ -236,10 +240,13 @@ extern "C" sparq_status sparq_conv_plan(const sparq_conv_desc* desc, const sparq
                  (pl.ws && !pl.split_log2) ? " wave_specialised" : "", pl.pad_bytes ? " padded_copy" : "");
     } else {
         const char* name = "?";
-        const TileLauncher fn = pick_tile(g);
+        ConvGeom gt = g.fold ? folded_view(g) : g;
+        gt.Np = g.Np;
+        const TileLauncher fn = pick_tile(gt);
         for (const TileEntry& t : kTiles)
             if (t.fn == fn) name = t.name;
-        snprintf(text, text_bytes, "conv_gemm_kernel tile=%s%s", name, pl.pad_bytes ? " padded_copy" : "");
+        snprintf(text, text_bytes, "conv_gemm_kernel tile=%s%s%s", name, pl.pad_bytes ? " padded_copy" : "",
+                 g.fold ? " pixel_folded" : "");
     }
     return SPARQ_OK;
 }
@@ -266,6 +273,30 @@ extern "C" sparq_status sparq_conv_gemm(const uint8_t* x, const void* packed_w, 
     const uint8_t* xin = x;
     TrimKind kind = trim_kind(mode);
     size_t x_bytes = g.x_bytes;
+    if (g.fold) {
+        // A first-layer shape (C <= 4): trim into a copy with 4 channels per pixel, then contract the
+        // pixel-folded problem (16-channel super-pixels, fold_p * N output channels) with trimming off.
+        const ConvGeom f = folded_view(g);
+        if (f.x_bytes >= kInvalidOffset) return SPARQ_EUNSUPPORTED;
+        const sparq_status st = launch_trim_pad(x, static_cast<uint8_t*>(workspace), (int64_t)g.B * g.H * g.W, g.C, 4, mode, s);
+        if (st != SPARQ_OK) return st;
+        GemmParams p{};
+        p.x = static_cast<const uint8_t*>(workspace);
+        p.wpk = static_cast<const uint8_t*>(packed_w) + g.w_off;
+        p.colsum = static_cast<const int32_t*>(packed_w);
+        p.acc = acc; p.scale = scale; p.out = out;
+        p.M = f.M;
+        p.x_bytes = (uint32_t)f.x_bytes;
+        p.N = f.N; p.Np = g.Np; p.Kk = f.Kk; p.nkb = g.Kp / kStepK; p.scale_n = g.N;
+        p.H = f.H; p.W = f.W; p.C = 16; p.Cq = 16; p.Ho = f.Ho; p.Wo = f.Wo; p.KH = f.KH; p.KW = f.KW;
+        p.sh = f.sh; p.sw = 1; p.ph = f.ph; p.pw = f.pw;
+        p.rcp_c = 1.0f / 16.0f;
+        p.rcp_kw = 1.0f / (float)f.KW;
+        p.luts = make_luts(8, 1);
+        ConvGeom ft = f;
+        ft.Np = g.Np;
+        return pick_tile(ft)(kTrimNone, p, s);
+    }
     if (g.Cp != g.C) {
         // Channel counts that are not a multiple of 16: trim into a channel-padded copy
         // first (pairs stay inside the row; padded channels are zeros with zero weights),
@@ -322,7 +353,7 @@ extern "C" sparq_status sparq_conv_gemm(const uint8_t* x, const void* packed_w, 
     p.out = out;
     p.M = g.M;
     p.x_bytes = (uint32_t)x_bytes;
-    p.N = g.N; p.Np = g.Np; p.Kk = g.Kk; p.nkb = g.Kp / kStepK;
+    p.N = g.N; p.Np = g.Np; p.Kk = g.Kk; p.nkb = g.Kp / kStepK; p.scale_n = g.N;
     p.H = g.H; p.W = g.W; p.C = g.Cp; p.Cq = g.Cq; p.Ho = g.Ho; p.Wo = g.Wo; p.KH = g.KH; p.KW = g.KW;
     p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw;
     p.rcp_c = 1.0f / (float)g.Cq;

@@ -36,6 +36,7 @@ struct GemmParams {
     int64_t M;
     uint32_t x_bytes;
     int N, Np, Kk, nkb;
+    int scale_n;             // scale[] has this many entries and is indexed by n % scale_n (pixel-folded layers repeat it)
     int H, W, C, Cq, Ho, Wo, KH, KW, sh, sw, ph, pw;   // C: channels per pixel in x; Cq: per tap in the packed weights
     int tiles_m, tiles_n;
     float rcp_c, rcp_kw;     // 1/Cq and 1/KW for the branch-free reduction-index decode
@@ -275,7 +276,7 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
             const int n = n0 + wn * Cfg::kWTN + j * 32 + l32;
             if (n >= p.N) continue;
             const int32_t corr = 128 * p.colsum[n];
-            const float sc = p.out ? p.scale[n] : 0.0f;
+            const float sc = p.out ? p.scale[n % p.scale_n] : 0.0f;
 #pragma unroll
             for (int i = 0; i < FM; ++i) {
                 const int64_t mb = m0 + wm * Cfg::kWTM + i * 32 + 4 * lhi;

@@ -172,16 +172,43 @@ __global__ __launch_bounds__(kEwThreads) void pack_weights_kernel(const int8_t* 
     }
 }
 
-// colsum[n] = sum_k w[n][k]; one wavefront per output channel
+// Weights of a pixel-folded layer (ConvGeom::fold): output channel n' = p * N + n of the folded
+// problem holds, at tap (kh, kwf) and folded channel 4 * q + c, the weight w[n][kh][kw][c] of the
+// original tap kw that super-pixel slot q lines up with for output class p (zero where there is none).
+__global__ __launch_bounds__(kEwThreads) void pack_weights_fold_kernel(const int8_t* __restrict__ w, uint4* __restrict__ dst,
+                                                                       int N, int Np, int C, int KH, int KW, int Kp,
+                                                                       int P, int KWf, int kw_min, int sw, int pw) {
+    const int64_t total = (int64_t)(Kp / kChunk) * Np;
+    const int64_t stride = (int64_t)gridDim.x * kEwThreads;
+    for (int64_t i = (int64_t)blockIdx.x * kEwThreads + threadIdx.x; i < total; i += stride) {
+        const int nf = (int)(i % Np);
+        const int tap = (int)(i / Np);              // one 16-byte chunk = one folded tap (kh, kwf)
+        const int kh = tap / KWf, kwf = tap - kh * KWf;
+        uint32_t v[4] = {0, 0, 0, 0};
+        if (nf < P * N && kh < KH) {
+            const int p = nf / N, n = nf - p * N;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int kw = 4 * (kwf + kw_min) + q - (sw * p - pw);
+                if (kw < 0 || kw >= KW) continue;
+                const int8_t* src = w + (((int64_t)n * KH + kh) * KW + kw) * C;
+                for (int c = 0; c < C; ++c) v[q] |= (uint32_t)(uint8_t)src[c] << (8 * c);
+            }
+        }
+        dst[i] = make_uint4(v[0], v[1], v[2], v[3]);
+    }
+}
+
+// colsum[n] = sum_k w[n % N][k]; one wavefront per (possibly replicated) output channel
 __global__ __launch_bounds__(64) void weight_colsum_kernel(const int8_t* __restrict__ w, int32_t* __restrict__ colsum, int N,
-                                                           int Np, int K) {
-    const int n = blockIdx.x;
+                                                           int Nrep, int K) {
+    const int n = (int)blockIdx.x < Nrep ? (int)blockIdx.x % N : N;
     int32_t s = 0;
     if (n < N)
         for (int k = threadIdx.x; k < K; k += 64) s += w[(int64_t)n * K + k];
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off, 64);
-    if (threadIdx.x == 0) colsum[n] = s;
+    if (threadIdx.x == 0) colsum[blockIdx.x] = s;
 }
 
 }  // namespace sparq
@@ -256,10 +283,15 @@ extern "C" sparq_status sparq_pack_weights(const int8_t* w, const sparq_conv_des
     if (packed_bytes < g.packed_bytes) return SPARQ_EWORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint8_t* base = static_cast<uint8_t*>(packed);
-    weight_colsum_kernel<<<g.Np, 64, 0, s>>>(w, reinterpret_cast<int32_t*>(base), g.N, g.Np, g.K);
+    weight_colsum_kernel<<<g.Np, 64, 0, s>>>(w, reinterpret_cast<int32_t*>(base), g.N, g.fold_p * g.N, g.K);
     const int64_t chunks = (int64_t)(g.Kp / kChunk) * g.Np;
-    pack_weights_kernel<<<ew_grid(chunks, kEwThreads), kEwThreads, 0, s>>>(
-        w, reinterpret_cast<uint4*>(base + g.w_off), g.N, g.Np, g.C, g.Cq, g.KH * g.KW, g.Kp);
+    if (g.fold)
+        pack_weights_fold_kernel<<<ew_grid(chunks, kEwThreads), kEwThreads, 0, s>>>(
+            w, reinterpret_cast<uint4*>(base + g.w_off), g.N, g.Np, g.C, g.KH, g.KW, g.Kp, g.fold_p, g.fold_kw,
+            g.fold_kw_min, g.sw, g.pw);
+    else
+        pack_weights_kernel<<<ew_grid(chunks, kEwThreads), kEwThreads, 0, s>>>(
+            w, reinterpret_cast<uint4*>(base + g.w_off), g.N, g.Np, g.C, g.Cq, g.KH * g.KW, g.Kp);
     return launch_status();
 }
 

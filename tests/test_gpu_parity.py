@@ -134,6 +134,13 @@ SHAPES = [
     S.ConvLayer("odd_c3_7x7", 2, 20, 20, 3, 16, 7, 7, (2, 2), (3, 3)),
     S.ConvLayer("odd_c159_n161", 1, 6, 17, 159, 161, 1, 7, (1, 1), (0, 3)),
     S.ConvLayer("wide_n", 1, 140, 1, 128, 520),
+    # at most 4 channels: the pixel-folded first-layer path (and shapes that cannot fold)
+    S.ConvLayer("thin_3x3_s1_c3", 2, 9, 16, 3, 10, 3, 3, (1, 1), (1, 1)),
+    S.ConvLayer("thin_5x5_s2_c4", 1, 12, 24, 4, 7, 5, 5, (2, 2), (2, 2)),
+    S.ConvLayer("thin_7x7_s2_c1", 3, 16, 32, 1, 64, 7, 7, (2, 2), (3, 3)),
+    S.ConvLayer("thin_3x3_s2_c2_n130", 2, 10, 40, 2, 130, 3, 3, (2, 2), (1, 1)),
+    S.ConvLayer("thin_s4_no_fold", 1, 16, 32, 1, 5, 3, 3, (4, 4), (1, 1)),
+    S.ConvLayer("thin_w18_no_fold", 1, 7, 18, 3, 9, 3, 3, (1, 1), (1, 1)),
 ]
 
 
