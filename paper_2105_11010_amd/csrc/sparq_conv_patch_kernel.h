@@ -246,6 +246,7 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
                 for (int v = 0; v < 16; ++v) c[i][j][v] = 0;
     };
     v4i b_reg[2][2][FN];          // weights of the current and the next step: [step parity][half][fragment]
+    int w_next = 0;               // weight offset of the step two ahead, computed one step early
     v4i a_frag[2][2][FM];         // activation fragments: [step parity][half][fragment]
 
     // ---- prologue: unit 0 staged, unit 1 requested, two weight steps requested ----
@@ -261,6 +262,7 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
         const int w1 = next_b_offset();
         load_b(b_reg[1][0], w1, 0);
         load_b(b_reg[1][1], w1, 1);
+        w_next = next_b_offset();
     }
     stage_npix = lt.npix;
     if (!WS || producer) {
@@ -283,9 +285,8 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
     // scheduling regions keep the compiler from sinking the loads next to their uses.
     auto step = [&](auto A_, v4i (&cur)[2][FM], v4i (&nxt)[2][FM], v4i (&br)[2][FN], const uint8_t* rbuf, uint8_t* sbuf) __attribute__((always_inline)) {
         constexpr int A = decltype(A_)::value;
-        advance_frag_cursor();
-        load_frags(nxt, rbuf);
-        const int wstep = next_b_offset();
+        load_frags(nxt, rbuf);                      // f_off already points at the next step
+        const int wstep = w_next;
 #pragma unroll
         for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -297,6 +298,10 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
             load_chunk(2 * A);
         }
         __builtin_amdgcn_sched_barrier(0);
+        // The cursor arithmetic of the following step (scalar instructions) is issued between this
+        // half's matrix instructions, where it is free, instead of in front of the next step's.
+        advance_frag_cursor();
+        w_next = next_b_offset();
 #pragma unroll
         for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -306,6 +311,11 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
         if constexpr (A >= 0 && 2 * A + 1 < AC) {
             stage_chunk(2 * A + 1, sbuf);
             load_chunk(2 * A + 1);
+        }
+#pragma unroll
+        for (int k = 0; k < FM * FN; ++k) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                    // one matrix instruction
+            __builtin_amdgcn_sched_group_barrier(0x004, (40 + FM * FN - 1) / (FM * FN), 0);   // a slice of the scalar work
         }
         __builtin_amdgcn_sched_barrier(0);
     };
@@ -329,6 +339,7 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
         }
         f_j = f_kw = f_kh = f_off = 0;
         load_frags(a_frag[P], rbuf);
+        advance_frag_cursor();
         auto head = [&](auto self, auto s_) __attribute__((always_inline)) {
             constexpr int s0 = decltype(s_)::value;
             if constexpr (s0 < U0) {
