@@ -296,6 +296,16 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
         if constexpr (A >= 0) {
             stage_chunk(2 * A, sbuf);
             load_chunk(2 * A);
+        } else {
+            // plain step: the fragment reads and weight requests of this half are independent of its
+            // matrix instructions; issue them in between rather than in front
+#pragma unroll
+            for (int k = 0; k < FM * FN; ++k) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                            // one matrix instruction
+                __builtin_amdgcn_sched_group_barrier(0x100, (2 * FM + FM * FN - 1) / (FM * FN), 0);   // fragment reads
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);                            // their address adds
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                            // a weight request
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
         // The cursor arithmetic of the following step (scalar instructions) is issued between this
