@@ -54,7 +54,9 @@ def parse_args():
     ap.add_argument("--batch", type=int, default=None, help="cfg1/2/4: batch override")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-layer", action="store_true", help="print a per-layer table on stderr")
-    ap.add_argument("--no-extra", action="store_true", help="skip the secondary ResNet-18 figure of the default run")
+    ap.add_argument("--no-extra", action="store_true", help="skip the secondary figures of the default run")
+    ap.add_argument("--sweep-form", default="conv", choices=["conv", "explicit"],
+                    help="cfg3-sweep: run the points as the 3x3 convolution (default) or on a materialised A[M,K]")
     return ap.parse_args()
 
 
@@ -152,9 +154,12 @@ def sweep(args, sq, S, torch, dev):
     tot_ops = tot_ms = 0.0
     for zf, modes in by_zf.items():
         base = replace(S.config3_layer(args.rows), zf=zf)
+        if args.sweep_form == "conv":
+            base = replace(base, name="conv3x3_512_512_32x32", B=args.rows // 1024, H=32, W=32, C=512, KH=3, KW=3, pad=(1, 1))
         items = prepare(sq, S, torch, dev, 3, [base])
         it = items[0]
         y = torch.empty_like(it["x"])
+        time_steps(sq, torch, items, args.warmup, args.warmup)     # clocks settle after the idle upload phase
         for mode in modes:
             it["layer"] = replace(base, mode=mode)
             it["m"] = sq.mode(*mode.astuple())
@@ -180,8 +185,8 @@ def sweep(args, sq, S, torch, dev):
         "metric": "SPARQ conv-GEMM TOPS (int8-equiv)", "value": round(tops, 2), "unit": "TOPS", "n_gpus": 1,
         "steps": max(10, args.steps // 10), "warmup": max(5, args.warmup // 5), "ms_per_step": round(tot_ms / len(points), 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
-        "config": {"workload": f"config3 sweep: {len(points)} option points on GEMM M={args.rows} K=4608 N=512 "
-                               "(value = total ops / total time over the points)"},
+        "config": {"workload": f"config3 sweep: {len(points)} option points on GEMM M={args.rows} K=4608 N=512, "
+                               f"{args.sweep_form} form (value = total ops / total time over the points)"},
         "points": points, "roofline": None, "cpu_baseline": None}), flush=True)
 
 
