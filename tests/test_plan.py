@@ -1,0 +1,81 @@
+"""Host-side planning of the convolution (no GPU): every layer of the workload tables gets a plan,
+and the plan agrees with the workspace the library asks for."""
+import ctypes
+import os
+
+import pytest
+
+import sparq_synth as S
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB = os.path.join(os.path.dirname(HERE), "paper_2105_11010_amd", "libsparq.so")
+
+
+class Mode(ctypes.Structure):
+    _fields_ = [("window_bits", ctypes.c_int32), ("shift_mask", ctypes.c_uint32),
+                ("round_nearest", ctypes.c_int32), ("pair", ctypes.c_int32)]
+
+
+class Desc(ctypes.Structure):
+    _fields_ = [(k, ctypes.c_int32) for k in
+                ("B", "H", "W", "C", "N", "KH", "KW", "stride_h", "stride_w", "pad_h", "pad_w")]
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        pytest.skip("libsparq.so not built")
+    L = ctypes.CDLL(LIB)
+    L.sparq_workspace_bytes.restype = ctypes.c_size_t
+    L.sparq_packed_bytes.restype = ctypes.c_size_t
+    return L
+
+
+def plan(lib, l, mode=None):
+    for k in ("SPARQ_PATH", "SPARQ_PATCH_TN", "SPARQ_PATCH_WS", "SPARQ_SPLIT", "SPARQ_TILE"):
+        os.environ.pop(k, None)
+    d = Desc(l.B, l.H, l.W, l.C, l.N, l.KH, l.KW, l.stride[0], l.stride[1], l.pad[0], l.pad[1])
+    m = Mode(*(mode or l.mode).astuple())
+    buf = ctypes.create_string_buffer(256)
+    assert lib.sparq_conv_plan(ctypes.byref(d), ctypes.byref(m), buf, len(buf)) == 0
+    return buf.value.decode(), lib.sparq_workspace_bytes(ctypes.byref(d), ctypes.byref(m)), lib.sparq_packed_bytes(ctypes.byref(d))
+
+
+ALL = [(c, l) for c, ls in ((0, S.config0()), (1, S.config1()), (2, S.config2()), (4, S.config4())) for l in ls]
+
+
+@pytest.mark.parametrize("cfg,layer", ALL, ids=lambda v: v.name if hasattr(v, "name") else f"cfg{v}")
+def test_every_workload_layer_has_a_consistent_plan(lib, cfg, layer):
+    text, ws, packed = plan(lib, layer)
+    assert text.startswith(("conv_patch_kernel", "conv_gemm_kernel"))
+    pixels = layer.B * layer.H * layer.W
+    if layer.C <= 4:
+        assert "pixel_folded" in text and ws >= pixels * 4           # 4-channel padded copy
+    elif layer.C % 16:
+        assert "padded_copy" in text and ws >= pixels * ((layer.C + 15) // 16 * 16)
+    else:
+        assert "padded_copy" not in text
+    if "split=1" in text or text.startswith("conv_gemm_kernel"):
+        if layer.C % 16 == 0:
+            assert ws == 0                                            # nothing to stage, nothing to sum
+    else:
+        assert ws >= layer.M * layer.N * 4                           # room for the split reduction's partial sums
+    assert packed >= layer.K * layer.N
+
+
+def test_plan_of_the_headline_shapes(lib):
+    conv = S.ConvLayer("conv3x3", 64, 32, 32, 512, 512, 3, 3, (1, 1), (1, 1), 0.5, S.Mode(4, S.OPT5, 1, 1))
+    text, ws, _ = plan(lib, conv)
+    assert text.startswith("conv_patch_kernel tile=128x256") and "wave_specialised" in text and ws == 0
+    text, ws, _ = plan(lib, S.config3_layer())
+    assert text.startswith("conv_gemm_kernel tile=128x512") and ws == 0
+
+
+def test_plan_rejects_bad_arguments(lib):
+    buf = ctypes.create_string_buffer(64)
+    m = Mode(4, 0x1F, 1, 1)
+    bad = Desc(1, 2, 2, 64, 64, 3, 3, 1, 1, 0, 0)
+    assert lib.sparq_conv_plan(ctypes.byref(bad), ctypes.byref(m), buf, len(buf)) == 1
+    ok = Desc(1, 8, 8, 64, 64, 3, 3, 1, 1, 1, 1)
+    assert lib.sparq_conv_plan(ctypes.byref(ok), ctypes.byref(m), None, 0) == 1
+    assert lib.sparq_conv_plan(ctypes.byref(ok), ctypes.byref(Mode(5, 1, 0, 0)), buf, len(buf)) == 1
