@@ -53,6 +53,7 @@ struct PatchParams {
     TrimLuts luts;
 };
 
+constexpr int kLdsPerCu = 160 * 1024;
 constexpr uint32_t kPatchInvalidOffset = 0x80000000u;   // beyond any buffer this kernel accepts (< 2 GiB)
 
 // TN output channels per workgroup, WGM x WGN wavefronts, AC 16-byte patch chunks per lane and
@@ -249,13 +250,49 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
     int w_next = 0;               // weight offset of the step two ahead, computed one step early
     v4i a_frag[2][2][FM];         // activation fragments: [step parity][half][fragment]
 
+    // ---- staging wavefronts (wave-specialised form): a loop of their own, so that their registers
+    //      and those of the matrix wavefronts do not add up; both loops pass the same barriers ----
+    if constexpr (WS) {
+        if (producer) {
+            load_tile_patch();
+#pragma unroll
+            for (int i = 0; i < AC; ++i) load_chunk(i);
+            stage_npix = lt.npix;
+#pragma unroll
+            for (int i = 0; i < AC; ++i) stage_chunk(i, lds);
+            advance_load_cursor();
+            stage_npix = lt.npix;                     // unit 1 is staged while unit 0 is multiplied
+#pragma unroll
+            for (int i = 0; i < AC; ++i) load_chunk(i);
+            advance_load_cursor();
+            __syncthreads();
+            int p_tile = (int)blockIdx.x, p_cb = 0, p_buf = 0;     // the unit the matrix wavefronts are on
+            while (true) {
+                uint8_t* sbuf = lds + (p_buf ^ 1) * buf_bytes;
+#pragma unroll
+                for (int i = 0; i < AC; ++i) {    // trim and write the next unit's chunks, request those of the unit after it
+                    stage_chunk(i, sbuf);
+                    load_chunk(i);
+                }
+                p_buf ^= 1;
+                const bool tile_done = p_cb == p.ncb - 1;
+                __syncthreads();
+                if (tile_done) { p_cb = 0; p_tile += grid; } else { ++p_cb; }
+                stage_npix = lt.npix;             // the unit requested during the last unit is staged in the next
+                advance_load_cursor();
+                if (p_tile >= ntiles) break;
+            }
+            return;
+        }
+    }
+
     // ---- prologue: unit 0 staged, unit 1 requested, two weight steps requested ----
-    load_tile_patch();
-    if (!WS || producer) {
+    if constexpr (!WS) {
+        load_tile_patch();
 #pragma unroll
         for (int i = 0; i < AC; ++i) load_chunk(i);
     }
-    if (!producer) {
+    {
         const int w0 = next_b_offset();
         load_b(b_reg[0][0], w0, 0);
         load_b(b_reg[0][1], w0, 1);
@@ -264,18 +301,16 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
         load_b(b_reg[1][1], w1, 1);
         w_next = next_b_offset();
     }
-    stage_npix = lt.npix;
-    if (!WS || producer) {
+    if constexpr (!WS) {
+        stage_npix = lt.npix;
 #pragma unroll
         for (int i = 0; i < AC; ++i) stage_chunk(i, lds);
-    }
-    advance_load_cursor();
-    stage_npix = lt.npix;                         // unit 1 is staged while unit 0 is multiplied
-    if (!WS || producer) {
+        advance_load_cursor();
+        stage_npix = lt.npix;                         // unit 1 is staged while unit 0 is multiplied
 #pragma unroll
         for (int i = 0; i < AC; ++i) load_chunk(i);
+        advance_load_cursor();
     }
-    advance_load_cursor();
     setup_compute_tile();
     zero_acc();
     __syncthreads();
@@ -338,15 +373,6 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
     constexpr int U0 = Cfg::kUnrolled;
     auto run_unit = [&](auto P_, const uint8_t* rbuf, uint8_t* sbuf) __attribute__((always_inline)) {
         constexpr int P = decltype(P_)::value;
-        if (producer) {
-            // staging wavefronts: trim and write the next unit's chunks, request those of the unit after it
-#pragma unroll
-            for (int i = 0; i < AC; ++i) {
-                stage_chunk(i, sbuf);
-                load_chunk(i);
-            }
-            return;
-        }
         f_j = f_kw = f_kh = f_off = 0;
         load_frags(a_frag[P], rbuf);
         advance_frag_cursor();
@@ -369,7 +395,8 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
     int ubuf = 0;
     auto boundary = [&]() __attribute__((always_inline)) {
         ubuf ^= 1;
-        if (!producer && c_cb == p.ncb - 1) {
+        const bool tile_done = c_cb == p.ncb - 1;
+        if (tile_done) {
             // ---- epilogue: undo the -128 offset, store int32 and/or dequantised fp32 ----
             // Register v of fragment (i, j) is pixel 8*(v/4) + 4*lhi + v%4, channel l32: each store
             // instruction writes two full 128-byte runs of consecutive channels.
@@ -418,8 +445,10 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
             c_tile += grid;
             if (c_tile < ntiles) setup_compute_tile();
         }
-        stage_npix = lt.npix;                     // the unit requested during the last unit is staged in the next
-        advance_load_cursor();
+        if constexpr (!WS) {
+            stage_npix = lt.npix;                 // the unit requested during the last unit is staged in the next
+            advance_load_cursor();
+        }
     };
 
     while (true) {
@@ -434,7 +463,6 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
     }
 }
 
-constexpr int kLdsPerCu = 160 * 1024;
 
 // `p` carries everything except plane_stride and the tile counts; npix_max bounds TilePatch::npix.
 template <class Cfg, int KIND>
