@@ -92,18 +92,9 @@ int patch_npix_max(const PatchGeom& g) {
 bool plan_patch(const ConvGeom& g, PatchGeom* pg, int* npix, int* ac, int* cbs) {
     if (g.Cq % kStepK != 0) return false;                        // fewer than 33 channels: taps are not step-aligned
     if (g.M >= kPatchMaxDividend || (size_t)g.Kp * g.Np >= kPatchInvalidOffset) return false;
-    PatchGeom q{};
-    const bool gemm = g.KH == 1 && g.KW == 1 && g.sh == 1 && g.sw == 1 && g.ph == 0 && g.pw == 0;
-    if (gemm) {                                                  // 1x1, stride 1: one long row of pixels
-        q.B = 1; q.H = 1; q.W = (int)g.M; q.Ho = 1; q.Wo = (int)g.M; q.KH = q.KW = 1; q.sh = q.sw = 1;
-    } else {
-        q.B = g.B; q.H = g.H; q.W = g.W; q.Ho = g.Ho; q.Wo = g.Wo; q.KH = g.KH; q.KW = g.KW;
-        q.sh = g.sh; q.sw = g.sw; q.ph = g.ph; q.pw = g.pw;
-    }
-    q.M = (int)g.M;
-    q.Hv = q.H + 2 * q.ph;
+    if ((int64_t)g.B * g.H * g.W >= kPatchMaxDividend) return false;     // the pixel remap of strided 1x1 layers
+    PatchGeom q = make_patch_geom(g.B, g.H, g.W, g.KH, g.KW, g.sh, g.sw, g.ph, g.pw);
     if ((int64_t)q.B * q.Hv + q.KH >= kPatchMaxDividend) return false;
-    q.rcp_wo = 1.0f / (float)q.Wo; q.rcp_ho = 1.0f / (float)q.Ho; q.rcp_hv = 1.0f / (float)q.Hv;
     if (patch_npix_bound(q) > 4096) return false;               // far too large: skip the exact walk
     const int n = patch_npix_max(q);
     const int taps = q.KH * q.KW;
@@ -151,9 +142,15 @@ const PatchVariant* pick_patch(const ConvGeom& g, int ac, int cbs, int npix, boo
         if ((v == 64 || v == 128 || v == 256) && tile_fits(v, g)) tn = v;
     }
     if (const char* e = getenv("SPARQ_PATCH_WS")) *ws = atoi(e) != 0;
+    const bool strided_1x1 = g.KH == 1 && g.KW == 1 && (g.sh > 1 || g.sw > 1);    // pixel remap: staging wavefronts only
+    if (strided_1x1) {
+        if (tn == 64) tn = 128;
+        *ws = true;
+    }
     for (const PatchVariant& v : kPatchVariants)
         if (v.tn == tn && v.ac == ac && v.cbs == cbs) {
             if (!v.fn_ws) *ws = false;
+            if (strided_1x1 && !*ws) return nullptr;
             return &v;
         }
     return nullptr;
@@ -177,11 +174,11 @@ int pick_split_log2(const ConvGeom& g, const PatchVariant& v, int ncb) {
     return lg;
 }
 
-// 1x1 stride-1 layers with a long reduction have nothing to reuse between taps; when they also
+// 1x1 layers with a long reduction have nothing to reuse between taps; when they also
 // fill the chip with wide tiles and waste little on channel padding, the gather kernel's wider
 // tiles (each activation trimmed once for up to 512 output channels) are faster.
 bool prefer_gather(const ConvGeom& g) {
-    const bool gemm = g.KH == 1 && g.KW == 1 && g.sh == 1 && g.sw == 1 && g.ph == 0 && g.pw == 0;
+    const bool gemm = g.KH == 1 && g.KW == 1 && g.ph == 0 && g.pw == 0;      // any stride
     if (!gemm || g.K < 768) return false;
     const int tn = (g.N > 256 && tile_fits(512, g)) ? 512 : g.N > 128 ? 256 : 128;
     const int64_t tiles = (g.M + 127) / 128 * ((g.N + tn - 1) / tn);
@@ -214,7 +211,7 @@ ConvPlan make_plan(const ConvGeom& g) {
         pl.variant = pick_patch(g, pl.ac, pl.cbs, pl.npix, force_patch, &pl.ws);
         if (pl.variant) {
             pl.patch = true;
-            pl.split_log2 = pick_split_log2(g, *pl.variant, g.Cq / kStepK / pl.cbs);
+            pl.split_log2 = pl.pg.rm_wo ? 0 : pick_split_log2(g, *pl.variant, g.Cq / kStepK / pl.cbs);   // (strided 1x1: staging wavefronts only)
             if (pl.split_log2) pl.split_bytes = (size_t)round_up(g.M * g.N * 4, 256);
         }
     }

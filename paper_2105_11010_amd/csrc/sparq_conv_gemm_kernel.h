@@ -242,6 +242,16 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
             load_b(br[0], 0);
             constexpr int kFirst = Cfg::kSplitTrim ? AC / 2 : 0;
             store_a(st2, a_old, 0, kFirst);
+            // issue the fragment reads, the gather's address arithmetic and the weight requests between the
+            // matrix instructions rather than in front of them (not for the largest tile: no registers
+            // to spare for the longer live ranges)
+#pragma unroll
+            for (int k = 0; k < (FM * FN * 16 <= 128 ? FM * FN : 0); ++k) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, (2 * FM + FM * FN - 1) / (FM * FN), 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, (48 + FM * FN - 1) / (FM * FN), 0);
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            }
             __builtin_amdgcn_sched_barrier(0);
             store_a(st2, a_old, kFirst, AC);
 #pragma unroll
@@ -251,6 +261,13 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
                     c[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur[1][i], br[1][j], c[i][j], 0, 0, 0);
             load_b(br[1], 1);
             advance_b();
+            // the trim arithmetic of this half (about 85 instructions per 16-byte chunk) goes between its
+            // matrix instructions as well
+#pragma unroll
+            for (int k = 0; k < (FM * FN * 16 <= 128 ? FM * FN : 0); ++k) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, (100 * AC + FM * FN - 1) / (FM * FN), 0);
+            }
             __builtin_amdgcn_sched_barrier(0);
             __syncthreads();
         };

@@ -151,7 +151,8 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
     auto load_chunk = [&](int i) __attribute__((always_inline)) {
         const int pix = my_pix + i * (NT / PL);
         const int ch = (l_cb0 + l_cb) * Cfg::kCB + my_c;
-        uint32_t off = patch_pixel_offset_u32(g, lt, pix, p.C, kPatchInvalidOffset);
+        // only the staging wavefronts of the wave-specialised form handle the pixel remap of strided 1x1 layers
+        uint32_t off = patch_pixel_offset_u32<WS>(g, lt, pix, p.C, kPatchInvalidOffset);
         off = (ch < p.C) ? off : kPatchInvalidOffset;            // a tap's channel padding reads as zero
         off += (off != kPatchInvalidOffset) ? (uint32_t)ch : 0u;
         a_reg[i] = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, (int)off, 0, 0);   // out of range reads 0
@@ -471,6 +472,7 @@ sparq_status launch_patch_cfg(const PatchParams& p, int npix_max, hipStream_t s)
     q.plane_stride = patch_plane_stride(npix_max, Cfg::kPlanes);
     const int lds_bytes = 2 * Cfg::kPlanes * q.plane_stride + kChunk;     // two patch buffers + the dummy chunk
     if ((p.split_log2 != 0) != Cfg::kSplitK) return SPARQ_EUNSUPPORTED;
+    if (p.g.rm_wo && !Cfg::kWaveSpecialised) return SPARQ_EUNSUPPORTED;
     if (npix_max > Cfg::kMaxPix || lds_bytes > kLdsPerCu || q.nsteps < Cfg::kUnrolled ||
         ((q.nsteps - Cfg::kUnrolled) & 1))
         return SPARQ_EUNSUPPORTED;

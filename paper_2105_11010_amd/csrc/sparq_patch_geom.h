@@ -32,7 +32,15 @@ struct PatchGeom {                          // per launch
     int B, H, W, Ho, Wo, KH, KW, sh, sw, ph, pw;
     int Hv;                                 // H + 2 * ph
     float rcp_wo, rcp_ho, rcp_hv;
+    // 1x1 filters without padding are run as one long row of M pixels (B = H = 1, W = M).  With a
+    // stride the m-th pixel of that row is pixel (oy * rm_sh, ox * rm_sw) of image b in the real
+    // tensor, m = (b * rm_ho + oy) * rm_wo + ox; rm_wo == 0: no stride, the row is the tensor itself.
+    int rm_wo, rm_ho, rm_h, rm_w, rm_sh, rm_sw;
+    float rm_rcp_wo, rm_rcp_ho;
 };
+
+// Pixel index of the m-th pixel of the long row in the real tensor (see PatchGeom::rm_wo).
+SPARQ_GEOM_HD int remap_pixel(const PatchGeom& g, int m);
 
 struct TilePatch {                          // per tile, uniform over the workgroup
     int m0;                                 // first output pixel
@@ -54,6 +62,35 @@ SPARQ_GEOM_HD int div_rcp(int a, int d, float rcp, int* rem) {
     q += hi;
     r -= hi ? d : 0;
     *rem = r;
+    return q;
+}
+
+SPARQ_GEOM_HD int remap_pixel(const PatchGeom& g, int m) {
+    int ox, oy;
+    const int r = div_rcp(m, g.rm_wo, g.rm_rcp_wo, &ox);
+    const int b = div_rcp(r, g.rm_ho, g.rm_rcp_ho, &oy);
+    return (b * g.rm_h + oy * g.rm_sh) * g.rm_w + ox * g.rm_sw;
+}
+
+// The geometry the patch kernel runs a convolution with (set-up shared by the library and its host test).
+// 1x1 filters without padding become one long row (with a pixel remap when strided).
+inline PatchGeom make_patch_geom(int B, int H, int W, int KH, int KW, int sh, int sw, int ph, int pw) {
+    PatchGeom q{};
+    const int Ho = (H + 2 * ph - KH) / sh + 1, Wo = (W + 2 * pw - KW) / sw + 1;
+    const int M = B * Ho * Wo;
+    if (KH == 1 && KW == 1 && ph == 0 && pw == 0) {
+        q.B = 1; q.H = 1; q.W = M; q.Ho = 1; q.Wo = M; q.KH = q.KW = 1; q.sh = q.sw = 1;
+        if (sh != 1 || sw != 1) {
+            q.rm_wo = Wo; q.rm_ho = Ho; q.rm_h = H; q.rm_w = W; q.rm_sh = sh; q.rm_sw = sw;
+            q.rm_rcp_wo = 1.0f / (float)Wo; q.rm_rcp_ho = 1.0f / (float)Ho;
+        }
+    } else {
+        q.B = B; q.H = H; q.W = W; q.Ho = Ho; q.Wo = Wo; q.KH = KH; q.KW = KW;
+        q.sh = sh; q.sw = sw; q.ph = ph; q.pw = pw;
+    }
+    q.M = M;
+    q.Hv = q.H + 2 * q.ph;
+    q.rcp_wo = 1.0f / (float)q.Wo; q.rcp_ho = 1.0f / (float)q.Ho; q.rcp_hv = 1.0f / (float)q.Hv;
     return q;
 }
 
@@ -115,18 +152,22 @@ SPARQ_GEOM_HD int64_t patch_pixel_offset(const PatchGeom& g, const TilePatch& t,
     const int b = div_rcp(t.v0 + row, g.Hv, g.rcp_hv, &iyp);
     const int iy = iyp - g.ph, ix = t.xlo + px;
     const bool ok = (pix < t.npix) & (b < g.B) & ((unsigned)iy < (unsigned)g.H) & ((unsigned)ix < (unsigned)g.W);
-    const int64_t off = (((int64_t)b * g.H + iy) * g.W + ix) * C;
+    int64_t off = (((int64_t)b * g.H + iy) * g.W + ix) * C;
+    if (g.rm_wo) off = (int64_t)remap_pixel(g, ok ? ix : 0) * C;
     return ok ? off : -1;
 }
 
 // The same in 32-bit arithmetic for tensors below 2 GiB; `invalid` is returned in place of -1.
+// REMAP = false compiles the pixel remap of strided 1x1 layers out (callers that never see one).
+template <bool REMAP = true>
 SPARQ_GEOM_HD uint32_t patch_pixel_offset_u32(const PatchGeom& g, const TilePatch& t, int pix, int C, uint32_t invalid) {
     int px, iyp;
     const int row = div_rcp(pix, t.pwt, t.rcp_pwt, &px);
     const int b = div_rcp(t.v0 + row, g.Hv, g.rcp_hv, &iyp);
     const int iy = iyp - g.ph, ix = t.xlo + px;
     const bool ok = (pix < t.npix) & (b < g.B) & ((unsigned)iy < (unsigned)g.H) & ((unsigned)ix < (unsigned)g.W);
-    const uint32_t off = (uint32_t)(((b * g.H + iy) * g.W + ix) * C);
+    uint32_t off = (uint32_t)(((b * g.H + iy) * g.W + ix) * C);
+    if (REMAP && g.rm_wo) off = (uint32_t)(remap_pixel(g, ok ? ix : 0) * C);
     return ok ? off : invalid;
 }
 

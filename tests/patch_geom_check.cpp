@@ -12,14 +12,10 @@ using namespace sparq;
 
 int main(int argc, char** argv) {
     if (argc < 10) return 2;
-    PatchGeom g{};
-    g.B = atoi(argv[1]); g.H = atoi(argv[2]); g.W = atoi(argv[3]); g.KH = atoi(argv[4]); g.KW = atoi(argv[5]);
-    g.sh = atoi(argv[6]); g.sw = atoi(argv[7]); g.ph = atoi(argv[8]); g.pw = atoi(argv[9]);
-    g.Ho = (g.H + 2 * g.ph - g.KH) / g.sh + 1;
-    g.Wo = (g.W + 2 * g.pw - g.KW) / g.sw + 1;
-    g.M = g.B * g.Ho * g.Wo;
-    g.Hv = g.H + 2 * g.ph;
-    g.rcp_wo = 1.0f / g.Wo; g.rcp_ho = 1.0f / g.Ho; g.rcp_hv = 1.0f / g.Hv;
+    const int B = atoi(argv[1]), H = atoi(argv[2]), W = atoi(argv[3]), KH = atoi(argv[4]), KW = atoi(argv[5]);
+    const int sh = atoi(argv[6]), sw = atoi(argv[7]), ph = atoi(argv[8]), pw = atoi(argv[9]);
+    const PatchGeom g = make_patch_geom(B, H, W, KH, KW, sh, sw, ph, pw);      // as the library sets it up
+    const int Ho = (H + 2 * ph - KH) / sh + 1, Wo = (W + 2 * pw - KW) / sw + 1;
     const int C = 16;
     const long long bound = patch_npix_bound(g);
     long long maxpix = 0;
@@ -29,14 +25,14 @@ int main(int argc, char** argv) {
         if (t.npix > maxpix) maxpix = t.npix;
         if (t.npix > bound) { printf("FAIL bound: tile %d npix %d > %lld\n", tiles, t.npix, bound); return 1; }
         for (int m = m0; m < m0 + kPatchTM && m < g.M; ++m) {
-            const int ox = m % g.Wo, oy = (m / g.Wo) % g.Ho, b = m / (g.Wo * g.Ho);
+            const int ox = m % Wo, oy = (m / Wo) % Ho, b = m / (Wo * Ho);
             const int base = patch_pixel_of_output(g, t, m);
-            for (int kh = 0; kh < g.KH; ++kh)
-                for (int kw = 0; kw < g.KW; ++kw) {
+            for (int kh = 0; kh < KH; ++kh)
+                for (int kw = 0; kw < KW; ++kw) {
                     const int pix = base + kh * t.pwt + kw;
                     if (pix < 0 || pix >= t.npix) { printf("FAIL range: m %d tap %d,%d pix %d npix %d\n", m, kh, kw, pix, t.npix); return 1; }
-                    const int iy = oy * g.sh - g.ph + kh, ix = ox * g.sw - g.pw + kw;
-                    const long long want = (iy < 0 || iy >= g.H || ix < 0 || ix >= g.W) ? -1 : (((long long)b * g.H + iy) * g.W + ix) * C;
+                    const int iy = oy * sh - ph + kh, ix = ox * sw - pw + kw;
+                    const long long want = (iy < 0 || iy >= H || ix < 0 || ix >= W) ? -1 : (((long long)b * H + iy) * W + ix) * C;
                     const long long got = patch_pixel_offset(g, t, pix, C);
                     if (got != want) { printf("FAIL map: m %d tap %d,%d got %lld want %lld\n", m, kh, kw, got, want); return 1; }
                     const uint32_t got32 = patch_pixel_offset_u32(g, t, pix, C, 0x80000000u);
