@@ -28,7 +28,7 @@ PEAK_INT8_TOPS = 5000.0     # MI355X dense int8 MFMA, published
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E, published
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of
-# this script (profiles/conv_gemm_cfg3_hbm_traffic.md).  FETCH_SIZE reads half the true figure on this
+# this script (summary under profiles/).  FETCH_SIZE reads half the true figure on this
 # chip (calibrated on the trim kernel, which reads and writes exactly the tensor's size), WRITE_SIZE
 # reads true KiB; the figures below are already scaled.
 MEASURED_TRAFFIC = {
@@ -194,7 +194,7 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(the path shards over output rows without communication, see DESIGN.md).", file=sys.stderr)
+              "(the path would shard over output rows / batch without any communication).", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
