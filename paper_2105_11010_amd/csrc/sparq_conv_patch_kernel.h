@@ -405,39 +405,73 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
             const int n0 = (c_tn >> p.split_log2) * TN;
             const int corr_mul = (c_tn & split_mask) == 0 ? 128 : 0;       // only the first split adds the offset term
             const float* scale_or_dummy = p.out ? p.scale : reinterpret_cast<const float*>(p.colsum);
-            // tiles that lie fully inside the M rows (all but the last) skip the per-row checks
-            auto store_tile = [&](auto full_) __attribute__((always_inline)) {
-                constexpr bool kFull = decltype(full_)::value;
+            if constexpr (Cfg::kSplitK) {
+                // partial sums of a split reduction: int32 adds commute, the result is exact
 #pragma unroll
                 for (int j = 0; j < FN; ++j) {
                     const int n = n0 + wn * Cfg::kWTN + j * 32 + l32;
                     if (n >= p.N) continue;
-                    // Both per-channel constants are loaded on every path (a load under a condition
-                    // makes the compiler put a full memory wait in front of every store below).
-                    int32_t corr = p.colsum[n] * corr_mul;
-                    float sc = scale_or_dummy[n];
-                    asm volatile("" : "+v"(corr), "+v"(sc));     // both loads have landed from here on
+                    const int32_t corr = p.colsum[n] * corr_mul;
 #pragma unroll
                     for (int i = 0; i < FM; ++i) {
                         const int64_t mb = m0 + wm * Cfg::kWTM + i * 32 + 4 * lhi;
 #pragma unroll
                         for (int v = 0; v < 16; ++v) {
                             const int64_t m = mb + 8 * (v / 4) + (v % 4);
-                            if (!kFull && m >= g.M) continue;
-                            const int32_t r = c[i][j][v] + corr;
-                            const int64_t o = m * p.N + n;
-                            if constexpr (Cfg::kSplitK) {   // partial sum of a split reduction: int32 adds commute, the result is exact
-                                __hip_atomic_fetch_add(p.acc + o, r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            } else {
-                                if (p.acc) p.acc[o] = r;
-                                if (p.out) p.out[o] = __fmul_rn((float)r, sc);
-                            }
+                            if (m >= g.M) continue;
+                            __hip_atomic_fetch_add(p.acc + m * p.N + n, c[i][j][v] + corr, __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
                         }
                     }
                 }
-            };
-            if (m0 + kPatchTM <= g.M) store_tile(std::true_type{});
-            else store_tile(std::false_type{});
+            } else {
+                // Buffer stores relative to the tile's first row: the lane's part of the offset is computed
+                // once, every row adds a uniform multiple of the row pitch, and rows past M or channels
+                // past N fall outside the buffer's range and are dropped by the hardware (no per-row
+                // branches, no 64-bit address arithmetic).  One copy per combination of outputs, chosen per tile.
+                const int rows = g.M - (int)m0 < kPatchTM ? g.M - (int)m0 : kPatchTM;
+                const int pitch = p.N * 4;
+                const int tile_bytes = rows * pitch;
+                uint32_t lane_off[FN];
+                int32_t corr[FN];
+                float sc[FN];
+#pragma unroll
+                for (int j = 0; j < FN; ++j) {
+                    const int n = n0 + wn * Cfg::kWTN + j * 32 + l32;
+                    const int nc = n < p.N ? n : 0;
+                    // both per-channel constants are loaded on every path (a load under a condition makes
+                    // the compiler put a full memory wait in front of every store below)
+                    corr[j] = p.colsum[nc] * corr_mul;
+                    sc[j] = scale_or_dummy[nc];
+                    lane_off[j] = n < p.N ? (uint32_t)((wm * Cfg::kWTM + 4 * lhi) * pitch + n * 4) : 0x80000000u;
+                }
+#pragma unroll
+                for (int j = 0; j < FN; ++j) asm volatile("" : "+v"(corr[j]), "+v"(sc[j]));   // loads have landed from here on
+                auto store_tile = [&](auto acc_, auto out_) __attribute__((always_inline)) {
+                    constexpr bool kAcc = decltype(acc_)::value, kOut = decltype(out_)::value;
+                    const __amdgpu_buffer_rsrc_t arsrc = __builtin_amdgcn_make_buffer_rsrc(
+                        kAcc ? (void*)(p.acc + m0 * p.N) : nullptr, 0, kAcc ? tile_bytes : 0, 0x00020000);
+                    const __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc(
+                        kOut ? (void*)(p.out + m0 * p.N) : nullptr, 0, kOut ? tile_bytes : 0, 0x00020000);
+#pragma unroll
+                    for (int i = 0; i < FM; ++i)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            const int row_bytes = (i * 32 + 8 * (v / 4) + (v % 4)) * pitch;
+#pragma unroll
+                            for (int j = 0; j < FN; ++j) {
+                                const int32_t r = c[i][j][v] + corr[j];
+                                const int off = (int)(lane_off[j] + (uint32_t)row_bytes);
+                                if constexpr (kAcc) __builtin_amdgcn_raw_buffer_store_b32(r, arsrc, off, 0, 0);
+                                if constexpr (kOut)
+                                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, __fmul_rn((float)r, sc[j])), orsrc, off, 0, 0);
+                            }
+                        }
+                };
+                if (p.acc && p.out) store_tile(std::true_type{}, std::true_type{});
+                else if (p.out) store_tile(std::false_type{}, std::true_type{});
+                else store_tile(std::true_type{}, std::false_type{});
+            }
             zero_acc();
         }
         __syncthreads();
@@ -473,6 +507,7 @@ sparq_status launch_patch_cfg(const PatchParams& p, int npix_max, hipStream_t s)
     const int lds_bytes = 2 * Cfg::kPlanes * q.plane_stride + kChunk;     // two patch buffers + the dummy chunk
     if ((p.split_log2 != 0) != Cfg::kSplitK) return SPARQ_EUNSUPPORTED;
     if (p.g.rm_wo && !Cfg::kWaveSpecialised) return SPARQ_EUNSUPPORTED;
+    if ((int64_t)p.N * 4 * kPatchTM >= 0x7FFFFFFF) return SPARQ_EUNSUPPORTED;   // 32-bit offsets inside a tile of results
     if (npix_max > Cfg::kMaxPix || lds_bytes > kLdsPerCu || q.nsteps < Cfg::kUnrolled ||
         ((q.nsteps - Cfg::kUnrolled) & 1))
         return SPARQ_EUNSUPPORTED;
