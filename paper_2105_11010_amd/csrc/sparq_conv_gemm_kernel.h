@@ -287,26 +287,48 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
 
         // ---- epilogue: undo the -128 offset, store int32 and/or dequantised fp32 ----
         // Register v of fragment (i, j) is pixel 8*(v/4) + 4*lhi + v%4, channel l32: each store
-        // instruction writes two full 128-byte runs of consecutive channels.
+        // instruction writes two full 128-byte runs of consecutive channels.  Buffer stores relative
+        // to the tile's first row: the lane's part of the offset is computed once, every row adds a
+        // uniform multiple of the row pitch, and rows past M or channels past N fall outside the
+        // buffer's range and are dropped by the hardware.  One copy per combination of outputs.
+        {
+            const int64_t left = p.M - m0;
+            const int rows = left < Cfg::kTM ? (int)left : Cfg::kTM;
+            const int pitch = p.N * 4;
+            const int tile_bytes = rows * pitch;
+            const float* scale_or_dummy = p.out ? p.scale : reinterpret_cast<const float*>(p.colsum);
+            auto store_tile = [&](auto acc_, auto out_) __attribute__((always_inline)) {
+                constexpr bool kAcc = decltype(acc_)::value, kOut = decltype(out_)::value;
+                const __amdgpu_buffer_rsrc_t arsrc = __builtin_amdgcn_make_buffer_rsrc(
+                    kAcc ? (void*)(p.acc + m0 * p.N) : nullptr, 0, kAcc ? tile_bytes : 0, 0x00020000);
+                const __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc(
+                    kOut ? (void*)(p.out + m0 * p.N) : nullptr, 0, kOut ? tile_bytes : 0, 0x00020000);
 #pragma unroll
-        for (int j = 0; j < FN; ++j) {
-            const int n = n0 + wn * Cfg::kWTN + j * 32 + l32;
-            if (n >= p.N) continue;
-            const int32_t corr = 128 * p.colsum[n];
-            const float sc = p.out ? p.scale[n % p.scale_n] : 0.0f;
+                for (int j = 0; j < FN; ++j) {
+                    const int n = n0 + wn * Cfg::kWTN + j * 32 + l32;
+                    const int nc = n < p.N ? n : 0;
+                    // both constants are loaded on every path (a load under a condition makes the
+                    // compiler put a full memory wait in front of every store below)
+                    int32_t corr = 128 * p.colsum[nc];
+                    float sc = scale_or_dummy[kOut ? nc % p.scale_n : nc];
+                    const uint32_t lane_off = n < p.N ? (uint32_t)((wm * Cfg::kWTM + 4 * lhi) * pitch + n * 4) : kInvalidOffset;
+                    asm volatile("" : "+v"(corr), "+v"(sc));
 #pragma unroll
-            for (int i = 0; i < FM; ++i) {
-                const int64_t mb = m0 + wm * Cfg::kWTM + i * 32 + 4 * lhi;
+                    for (int i = 0; i < FM; ++i)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int64_t m = mb + 8 * (v / 4) + (v % 4);
-                    if (m >= p.M) continue;
-                    const int32_t r = c[i][j][v] + corr;
-                    const int64_t o = m * p.N + n;
-                    if (p.acc) p.acc[o] = r;
-                    if (p.out) p.out[o] = __fmul_rn((float)r, sc);
+                        for (int v = 0; v < 16; ++v) {
+                            const int row_bytes = (i * 32 + 8 * (v / 4) + (v % 4)) * pitch;
+                            const int32_t r = c[i][j][v] + corr;
+                            const int off = (int)(lane_off + (uint32_t)row_bytes);
+                            if constexpr (kAcc) __builtin_amdgcn_raw_buffer_store_b32(r, arsrc, off, 0, 0);
+                            if constexpr (kOut)
+                                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, __fmul_rn((float)r, sc)), orsrc, off, 0, 0);
+                        }
                 }
-            }
+            };
+            if (p.acc && p.out) store_tile(std::true_type{}, std::true_type{});
+            else if (p.out) store_tile(std::false_type{}, std::true_type{});
+            else store_tile(std::true_type{}, std::false_type{});
         }
     }   // tile loop
 }
