@@ -38,12 +38,12 @@ TileLauncher pick_tile(const ConvGeom& g) {
 // ---- input-patch kernel: eligibility and variant choice --------------------------------------
 struct PatchVariant { int tn, ac, cbs; PatchLauncher fn; PatchLauncher fn_split; PatchLauncher fn_ws; };   // fn_split / fn_ws: null if not built
 const PatchVariant kPatchVariants[] = {
-    {64, 2, 1, launch_patch_n64_a2c1, nullptr, nullptr},
-    {64, 4, 1, launch_patch_n64_a4c1, nullptr, nullptr},
-    {64, 8, 1, launch_patch_n64_a8c1, nullptr, nullptr},
-    {64, 12, 1, launch_patch_n64_a12c1, nullptr, nullptr},
-    {64, 4, 2, launch_patch_n64_a4c2, nullptr, nullptr},
-    {64, 8, 4, launch_patch_n64_a8c4, nullptr, nullptr},
+    {64, 2, 1, launch_patch_n64_a2c1, nullptr, launch_patch_ws_n64_a2c1},
+    {64, 4, 1, launch_patch_n64_a4c1, nullptr, launch_patch_ws_n64_a4c1},
+    {64, 8, 1, launch_patch_n64_a8c1, nullptr, launch_patch_ws_n64_a8c1},
+    {64, 12, 1, launch_patch_n64_a12c1, nullptr, launch_patch_ws_n64_a12c1},
+    {64, 4, 2, launch_patch_n64_a4c2, nullptr, launch_patch_ws_n64_a4c2},
+    {64, 8, 4, launch_patch_n64_a8c4, nullptr, launch_patch_ws_n64_a8c4},
     {128, 2, 1, launch_patch_n128_a2c1, nullptr, launch_patch_ws_n128_a2c1},
     {128, 4, 1, launch_patch_n128_a4c1, launch_patch_split_n128_a4c1, launch_patch_ws_n128_a4c1},
     {128, 8, 1, launch_patch_n128_a8c1, launch_patch_split_n128_a8c1, launch_patch_ws_n128_a8c1},
@@ -118,7 +118,8 @@ bool plan_patch(const ConvGeom& g, PatchGeom* pg, int* npix, int* ac, int* cbs) 
 }
 
 // Output-channel tile and form of the patch kernel.
-//   64 for narrow layers; otherwise 128, two workgroups per CU that hide each other's latencies;
+//   64 for narrow layers (wave-specialised, two workgroups of 8 wavefronts per CU: the accumulators are small
+//   enough for 128 registers per lane); otherwise 128, two workgroups per CU that hide each other's latencies;
 //   256 (one workgroup per CU, wave-specialised: 4 matrix + 4 staging wavefronts) for long reductions over a
 //   multiple of 256 channels with tiles for at least half the chip; 256 in the plain form for patches so
 //   large that LDS holds one workgroup per CU anyway (strided 3x3 layers on large images) when the layer is
@@ -137,16 +138,14 @@ const PatchVariant* pick_patch(const ConvGeom& g, int ac, int cbs, int npix, boo
         else if (g.N < 256 && tiles_m * ((g.N + 127) / 128) >= cus && !forced) return nullptr;   // narrow: gather kernel
     }
     if (tn == 128 && tiles_m * ((g.N + 127) / 128) <= cus) *ws = small_patch;
+    if (tn == 64) *ws = true;                      // small accumulators: two wave-specialised workgroups share a CU
     if (const char* e = getenv("SPARQ_PATCH_TN")) {
         const int v = atoi(e);
         if ((v == 64 || v == 128 || v == 256) && tile_fits(v, g)) tn = v;
     }
     if (const char* e = getenv("SPARQ_PATCH_WS")) *ws = atoi(e) != 0;
     const bool strided_1x1 = g.KH == 1 && g.KW == 1 && (g.sh > 1 || g.sw > 1);    // pixel remap: staging wavefronts only
-    if (strided_1x1) {
-        if (tn == 64) tn = 128;
-        *ws = true;
-    }
+    if (strided_1x1) *ws = true;
     for (const PatchVariant& v : kPatchVariants)
         if (v.tn == tn && v.ac == ac && v.cbs == cbs) {
             if (!v.fn_ws) *ws = false;

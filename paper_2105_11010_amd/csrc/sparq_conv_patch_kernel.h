@@ -551,6 +551,12 @@ sparq_status launch_patch_kind(TrimKind kind, const PatchParams& p, int npix_max
 // One translation unit per tile shape instantiates every trim variant and exports a launcher.
 typedef sparq_status (*PatchLauncher)(TrimKind, const PatchParams&, int, hipStream_t);
 #define SPARQ_DECLARE_PATCH(name) sparq_status name(TrimKind kind, const PatchParams& p, int npix_max, hipStream_t s)
+SPARQ_DECLARE_PATCH(launch_patch_ws_n64_a2c1);
+SPARQ_DECLARE_PATCH(launch_patch_ws_n64_a4c1);
+SPARQ_DECLARE_PATCH(launch_patch_ws_n64_a8c1);
+SPARQ_DECLARE_PATCH(launch_patch_ws_n64_a12c1);
+SPARQ_DECLARE_PATCH(launch_patch_ws_n64_a4c2);
+SPARQ_DECLARE_PATCH(launch_patch_ws_n64_a8c4);
 SPARQ_DECLARE_PATCH(launch_patch_ws_n128_a2c1);
 SPARQ_DECLARE_PATCH(launch_patch_ws_n128_a4c1);
 SPARQ_DECLARE_PATCH(launch_patch_ws_n128_a8c1);

@@ -185,6 +185,9 @@ PATCH_SHAPES = [
     S.ConvLayer("p_3x3_s2_small", 6, 9, 9, 64, 32, 3, 3, (2, 2), (1, 1)),
     S.ConvLayer("p_3x3_p2_dilated_pad", 2, 6, 6, 64, 16, 3, 3, (1, 1), (2, 2)),
     S.ConvLayer("p_2x2_even_taps", 2, 10, 10, 64, 16, 2, 2, (1, 1), (0, 0)),
+    S.ConvLayer("p_1x1_s2_c64_n48", 3, 15, 13, 64, 48, 1, 1, (2, 2), (0, 0)),      # strided 1x1: pixel remap
+    S.ConvLayer("p_1x1_s2_c128_n200", 5, 14, 14, 128, 200, 1, 1, (2, 2), (0, 0)),
+    S.ConvLayer("p_1x1_s3x2_c256_n70", 2, 17, 19, 256, 70, 1, 1, (3, 2), (0, 0)),
 ]
 
 
