@@ -117,28 +117,28 @@ bool plan_patch(const ConvGeom& g, PatchGeom* pg, int* npix, int* ac, int* cbs) 
     return false;
 }
 
-// Output-channel tile and form of the patch kernel.
+// Output-channel tile and form of the patch kernel (rules fitted to per-layer measurements of the workload tables).
 //   64 for narrow layers (wave-specialised, two workgroups of 8 wavefronts per CU: the accumulators are small
-//   enough for 128 registers per lane); otherwise 128, two workgroups per CU that hide each other's latencies;
-//   256 (one workgroup per CU, wave-specialised: 4 matrix + 4 staging wavefronts) for long reductions over a
-//   multiple of 256 channels with tiles for at least half the chip; 256 in the plain form for patches so
-//   large that LDS holds one workgroup per CU anyway (strided 3x3 layers on large images) when the layer is
-//   wide and fills the chip.  A 128 tile whose layer has no more tiles than CUs runs alone on its CU: it
-//   takes the wave-specialised form as well (unless its reduction is split).
+//   enough for 128 registers per lane).
+//   256 (wave-specialised: 4 matrix + 4 staging wavefronts, one workgroup per CU) when it pads N to no more columns
+//   than 128-wide tiles would and either fills three quarters of the chip or the layer is small anyway (then one
+//   larger tile per CU beats a split reduction with its two extra launches); also for patches so large that LDS
+//   holds one workgroup per CU anyway (strided 3x3 layers on large images) when the layer is wide and fills the chip.
+//   128 otherwise: two plain workgroups per CU that hide each other's latencies for 1x1 layers with many tiles,
+//   wave-specialised for multi-tap layers and for layers with no more tiles than CUs.
 // SPARQ_PATCH_TN=<n> and SPARQ_PATCH_WS=0|1 (tuning knobs) force the choice.
 const PatchVariant* pick_patch(const ConvGeom& g, int ac, int cbs, int npix, bool forced, bool* ws) {
     const int64_t tiles_m = (g.M + kPatchTM - 1) / kPatchTM;
+    const int64_t t128 = tiles_m * ((g.N + 127) / 128), t256 = tiles_m * ((g.N + 255) / 256);
     const int cus = device_cu_count();
     int tn = g.N <= 64 ? 64 : 128;
-    *ws = false;
-    const bool small_patch = ac <= 8;              // staging a larger patch keeps four wavefronts busier than the matrix work
-    if (g.N >= 256 && g.N % 256 == 0 && g.K >= 2048 && tiles_m * (g.N / 256) * 2 >= cus) { tn = 256; *ws = small_patch; }
+    const bool same_columns = round_up(g.N, 256) == round_up(g.N, 128);
+    if (g.N > 128 && same_columns && (t256 * 4 >= (int64_t)cus * 3 || (t128 <= cus && t256 * 8 >= cus))) tn = 256;
     if (2 * 4 * cbs * patch_plane_stride(npix, 4 * cbs) > kLdsPerCu / 2) {
-        if (g.N >= 256 && tiles_m * ((g.N + 255) / 256) >= cus) { tn = 256; *ws = false; }
-        else if (g.N < 256 && tiles_m * ((g.N + 127) / 128) >= cus && !forced) return nullptr;   // narrow: gather kernel
+        if (g.N >= 256 && t256 >= cus) tn = 256;
+        else if (g.N < 256 && t128 >= cus && !forced) return nullptr;   // narrow: gather kernel
     }
-    if (tn == 128 && tiles_m * ((g.N + 127) / 128) <= cus) *ws = small_patch;
-    if (tn == 64) *ws = true;                      // small accumulators: two wave-specialised workgroups share a CU
+    *ws = tn != 128 || g.KH * g.KW > 1 || t128 <= cus;
     if (const char* e = getenv("SPARQ_PATCH_TN")) {
         const int v = atoi(e);
         if ((v == 64 || v == 128 || v == 256) && tile_fits(v, g)) tn = v;
