@@ -7,7 +7,8 @@ this package; the GPU library never does, and the two share no code.
 The C file follows the paper step by step: bSPARQ window placement and
 rounding (Section 3.1), the vSPARQ pair rule (Section 3.2, Eq. 2), the integer
 dot product of Eq. 1 laid out as a convolution, and the per-output-channel
-dequantisation implied by the quantisation scheme of Section 5.
+dequantisation and the requantisation to unsigned 8 bits implied by the
+quantisation scheme of Section 5.
 """
 from __future__ import annotations
 
@@ -66,6 +67,9 @@ def lib() -> ctypes.CDLL:
         L.sparq_dequant_ref.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                         ctypes.c_int64, ctypes.c_int32]
         L.sparq_dequant_ref.restype = ctypes.c_int
+        L.sparq_requant_ref.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                        ctypes.c_int64, ctypes.c_int32]
+        L.sparq_requant_ref.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -155,3 +159,22 @@ def dequant(acc: np.ndarray, scale: np.ndarray) -> np.ndarray:
     if rc:
         raise ValueError(f"sparq_dequant_ref rejected its arguments (code {rc})")
     return out
+
+
+def requant(acc: np.ndarray, factor: np.ndarray) -> np.ndarray:
+    """y = clamp(rint(float32(acc) * factor[n]), 0, 255) as uint8 (Section 5: unsigned per-layer activations)."""
+    acc = np.ascontiguousarray(acc, dtype=np.int32)
+    factor = np.ascontiguousarray(factor, dtype=np.float32)
+    M, N = acc.shape
+    y = np.empty((M, N), dtype=np.uint8)
+    rc = lib().sparq_requant_ref(_ptr(acc), _ptr(factor), _ptr(y), M, N)
+    if rc:
+        raise ValueError(f"sparq_requant_ref rejected its arguments (code {rc})")
+    return y
+
+
+def conv_gemm_u8(x: np.ndarray, w: np.ndarray, factor: np.ndarray, stride=(1, 1), pad=(0, 0), *, rows=None, **mode):
+    """The trimmed convolution followed by the requantisation of its int32 result: uint8 [M or len(rows), N]."""
+    acc, _ = conv_gemm(x, w, stride, pad, rows=rows, **mode)
+    return requant(acc, factor)
+

@@ -7,6 +7,7 @@
  */
 #include "sparq_oracle.h"
 
+#include <math.h>
 #include <stdlib.h>
 #include <string.h>
 
@@ -227,3 +228,34 @@ int sparq_dequant_ref(const int32_t *acc, const float *scale, double *out,
             out[m * N + n] = (double)acc[m * N + n] * (double)scale[n];
     return 0;
 }
+
+/* ------------------------------------------------------------------------ */
+/* requantisation to the next layer's activations (Section 5, first          */
+/* paragraph: uniform min-max quantisation, symmetric and unsigned per layer */
+/* for activations, so a layer's result is scaled, rounded and clamped to    */
+/* [0, 255]; factor[n] = input scale * weight scale of kernel n / output     */
+/* scale).  The paper does not fix the arithmetic: the product and the       */
+/* rounding (to nearest, ties to even) are taken in fp32, and the result is  */
+/* defined by exactly that arithmetic.                                        */
+/* ------------------------------------------------------------------------ */
+
+int sparq_requant_ref(const int32_t *acc, const float *factor, uint8_t *y,
+                      int64_t M, int32_t N)
+{
+    if (!acc || !factor || !y || M < 0 || N <= 0)
+        return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int32_t n = 0; n < N; ++n) {
+            const float a = (float)acc[m * N + n];   /* int32 -> fp32, round to nearest even     */
+            volatile float p = a * factor[n];        /* one fp32 product, not contracted, not kept wider */
+            float r = rintf(p);                      /* to nearest integer, ties to even          */
+            if (!(r >= 0.0f))
+                r = 0.0f;                            /* lower clamp: the unsigned range (the ReLU) */
+            if (r > 255.0f)
+                r = 255.0f;
+            y[m * N + n] = (uint8_t)r;
+        }
+    return 0;
+}
+

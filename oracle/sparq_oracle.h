@@ -4,7 +4,8 @@
  * A plain, slow, step-by-step host implementation of the SPARQ activation
  * trim (bSPARQ, Section 3.1; vSPARQ, Section 3.2, Eq. 1-2) followed by the
  * integer dot product of Eq. 1 arranged as a convolution, and the
- * per-output-channel dequantisation implied by the quantisation scheme of
+ * per-output-channel dequantisation and the requantisation to the next
+ * layer's unsigned 8-bit activations implied by the quantisation scheme of
  * Section 5.  It exists to check the GPU library and to serve as the timed
  * CPU baseline.  Nothing in the product path may call it, and it shares no
  * code, header, table or helper with the GPU library.
@@ -23,7 +24,9 @@
  *   - for n < 4 a value whose partner is zero gets a 2n-bit window (Section
  *     5.1, "total window sizes are 6 and 4 bits") whose allowed shifts are the
  *     t for which both t and t+n are allowed n-bit shifts (the two n-bit
- *     multipliers of Eq. 4 acting as the high and low half).
+ *     multipliers of Eq. 4 acting as the high and low half);
+ *   - requantisation rounds to nearest with ties to even, product and
+ *     rounding in fp32 (the paper names the quantiser, not its arithmetic).
  *
  * Parity status: the tie direction, the saturate-versus-renormalise choice
  * and the 2n-bit shift set are readings, not printed values -- they are
@@ -81,6 +84,10 @@ int sparq_conv_gemm_ref(const uint8_t *x, const int8_t *w,
 
 /* out[m][n] = (double)acc[m][n] * (double)scale[n] */
 int sparq_dequant_ref(const int32_t *acc, const float *scale, double *out,
+                      int64_t M, int32_t N);
+
+/* Requantisation to unsigned 8 bits: y = clamp(rint((float)acc * factor[n]), 0, 255), fp32, ties to even. */
+int sparq_requant_ref(const int32_t *acc, const float *factor, uint8_t *y,
                       int64_t M, int32_t N);
 
 #ifdef __cplusplus
