@@ -128,6 +128,29 @@ sparq_status sparq_conv_gemm(const uint8_t *x, const void *packed_w,
 sparq_status sparq_dequant(const int32_t *acc, const float *scale, float *out,
                            int64_t M, int32_t N, void *stream);
 
+/* The same convolution with its result requantised to the next layer's
+ * unsigned 8-bit activations (Section 5, first paragraph: uniform min-max
+ * quantisation, symmetric unsigned per layer for activations, symmetric signed
+ * per kernel for weights):
+ *   y[m][n] = clamp(round(acc[m][n] * factor[n]), 0, 255),
+ *   factor[n] = s_x * s_w[n] / s_y   (input scale, weight scale of kernel n, output scale),
+ * so that y is the NHWC uint8 input of the next layer and its lower clamp is
+ * the ReLU.  The product and the rounding (to nearest, ties to even) are done
+ * in fp32: y is defined by exactly that arithmetic.  Neither acc nor a float
+ * tensor is written: one byte leaves per output instead of four.  factor and y
+ * (both device memory) must be 16-byte aligned; everything else as for
+ * sparq_conv_gemm with acc == NULL, including the workspace. */
+sparq_status sparq_conv_gemm_u8(const uint8_t *x, const void *packed_w,
+                                const sparq_conv_desc *desc, const sparq_mode *mode,
+                                const float *factor, uint8_t *y,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
+/* The requantisation of sparq_conv_gemm_u8 as a pass of its own over int32
+ * accumulators: y[m][n] = clamp(round(acc[m][n] * factor[n]), 0, 255), fp32
+ * product, ties to even.  Device pointers; M may be 0. */
+sparq_status sparq_requant(const int32_t *acc, const float *factor, uint8_t *y,
+                           int64_t M, int32_t N, void *stream);
+
 /* Static description of a status code. */
 const char *sparq_strerror(sparq_status status);
 

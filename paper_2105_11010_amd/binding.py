@@ -56,6 +56,10 @@ def _load() -> ctypes.CDLL:
     L.sparq_conv_gemm.restype = ctypes.c_int
     L.sparq_dequant.argtypes = [vp, vp, vp, i64, i32, vp]
     L.sparq_dequant.restype = ctypes.c_int
+    L.sparq_conv_gemm_u8.argtypes = [vp, vp, pd, pm, vp, vp, vp, sz, vp]
+    L.sparq_conv_gemm_u8.restype = ctypes.c_int
+    L.sparq_requant.argtypes = [vp, vp, vp, i64, i32, vp]
+    L.sparq_requant.restype = ctypes.c_int
     L.sparq_strerror.argtypes = [ctypes.c_int]
     L.sparq_strerror.restype = ctypes.c_char_p
     return L
@@ -156,3 +160,27 @@ def sparq_dequant(acc: torch.Tensor, scale: torch.Tensor, out: torch.Tensor) -> 
         raise ValueError("shape mismatch")
     _check(lib.sparq_dequant(_dev(acc, torch.int32, "acc"), _dev(scale, torch.float32, "scale"),
                              _dev(out, torch.float32, "out"), M, N, _stream()), "sparq_dequant")
+
+
+def sparq_conv_gemm_u8(x: torch.Tensor, packed: torch.Tensor, d: SparqConvDesc, m: SparqMode, factor: torch.Tensor,
+                       y: torch.Tensor, workspace: Optional[torch.Tensor] = None) -> None:
+    """The convolution with its result requantised to uint8 (y holds M*N bytes: the next layer's NHWC input)."""
+    if x.numel() != d.B * d.H * d.W * d.C:
+        raise ValueError("activation size does not match the descriptor")
+    if y.numel() != out_rows(d) * d.N:
+        raise ValueError(f"y must hold M*N = {out_rows(d) * d.N} elements")
+    if factor.numel() != d.N:
+        raise ValueError("factor must hold N elements")
+    ws_ptr = _dev(workspace, torch.uint8, "workspace")
+    ws_bytes = workspace.numel() if workspace is not None else 0
+    _check(lib.sparq_conv_gemm_u8(_dev(x, torch.uint8, "x"), _dev(packed, torch.uint8, "packed"), ctypes.byref(d),
+                                  ctypes.byref(m), _dev(factor, torch.float32, "factor"), _dev(y, torch.uint8, "y"),
+                                  ws_ptr, ws_bytes, _stream()), "sparq_conv_gemm_u8")
+
+
+def sparq_requant(acc: torch.Tensor, factor: torch.Tensor, y: torch.Tensor) -> None:
+    M, N = acc.shape
+    if y.shape != acc.shape or factor.numel() != N:
+        raise ValueError("shape mismatch")
+    _check(lib.sparq_requant(_dev(acc, torch.int32, "acc"), _dev(factor, torch.float32, "factor"),
+                             _dev(y, torch.uint8, "y"), M, N, _stream()), "sparq_requant")

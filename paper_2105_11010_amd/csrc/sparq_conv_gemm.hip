@@ -26,11 +26,12 @@ const TileEntry kTiles[] = {
 // A tile shape is usable only if all its weight loads stay inside the padded buffer.
 bool tile_fits(int tn, const ConvGeom& g) { return round_up(g.N, tn) <= g.Np; }
 
-TileLauncher pick_tile(const ConvGeom& g) {
+// byte_output: the requantised uint8 output, which the 128x512 tile does not have.
+TileLauncher pick_tile(const ConvGeom& g, bool byte_output = false) {
     if (const char* e = getenv("SPARQ_TILE"))
         for (const TileEntry& t : kTiles)
-            if (!strcmp(e, t.name) && tile_fits(t.tn, g)) return t.fn;
-    if (g.N > 256 && tile_fits(512, g)) return kTiles[2].fn;
+            if (!strcmp(e, t.name) && tile_fits(t.tn, g) && !(byte_output && t.tn == 512)) return t.fn;
+    if (g.N > 256 && tile_fits(512, g) && !byte_output) return kTiles[2].fn;
     if (g.N > 128) return kTiles[1].fn;
     return kTiles[0].fn;
 }
@@ -247,20 +248,24 @@ extern "C" sparq_status sparq_conv_plan(const sparq_conv_desc* desc, const sparq
     return SPARQ_OK;
 }
 
-extern "C" sparq_status sparq_conv_gemm(const uint8_t* x, const void* packed_w, const sparq_conv_desc* desc,
-                                        const sparq_mode* mode, int32_t* acc, const float* scale, float* out,
-                                        void* workspace, size_t workspace_bytes, void* stream) {
+namespace {
+
+// Both convolution entry points: acc / out (with scale) as in sparq_conv_gemm, or y (with scale holding the
+// requantisation factors) as in sparq_conv_gemm_u8.
+sparq_status conv_launch(const uint8_t* x, const void* packed_w, const sparq_conv_desc* desc, const sparq_mode* mode,
+                         int32_t* acc, const float* scale, float* out, uint8_t* y, void* workspace,
+                         size_t workspace_bytes, void* stream) {
     ConvGeom g;
     if (!x || !packed_w || !conv_geom(desc, &g) || !mode_valid(mode)) return SPARQ_EINVAL;
-    if (!acc && !out) return SPARQ_EINVAL;
-    if (out && !scale) return SPARQ_EINVAL;
+    if (!acc && !out && !y) return SPARQ_EINVAL;
+    if ((out || y) && !scale) return SPARQ_EINVAL;
     if (!aligned(x, 16) || !aligned(packed_w, 256) || (acc && !aligned(acc, 16)) || (out && !aligned(out, 16)) ||
-        (scale && !aligned(scale, 16)))
+        (y && !aligned(y, 16)) || (scale && !aligned(scale, 16)))
         return SPARQ_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const ConvPlan pl = make_plan(g);
     const bool split = pl.patch && pl.split_log2 > 0;
-    const size_t need = pl.pad_bytes + ((split && !acc) ? pl.split_bytes : 0);
+    const size_t need = pl.pad_bytes + ((split && !acc) ? pl.split_bytes : 0);   // (y: acc is null)
     if (need) {
         if (!workspace || !aligned(workspace, 256)) return SPARQ_EINVAL;
         if (workspace_bytes < need) return SPARQ_EWORKSPACE;
@@ -280,7 +285,7 @@ extern "C" sparq_status sparq_conv_gemm(const uint8_t* x, const void* packed_w, 
         p.x = static_cast<const uint8_t*>(workspace);
         p.wpk = static_cast<const uint8_t*>(packed_w) + g.w_off;
         p.colsum = static_cast<const int32_t*>(packed_w);
-        p.acc = acc; p.scale = scale; p.out = out;
+        p.acc = acc; p.scale = scale; p.out = out; p.out_u8 = y;
         p.M = f.M;
         p.x_bytes = (uint32_t)f.x_bytes;
         p.N = f.N; p.Np = g.Np; p.Kk = f.Kk; p.nkb = g.Kp / kStepK; p.scale_n = g.N;
@@ -291,7 +296,7 @@ extern "C" sparq_status sparq_conv_gemm(const uint8_t* x, const void* packed_w, 
         p.luts = make_luts(8, 1);
         ConvGeom ft = f;
         ft.Np = g.Np;
-        return pick_tile(ft)(kTrimNone, p, s);
+        return pick_tile(ft, y != nullptr)(kTrimNone, p, s);
     }
     if (g.Cp != g.C) {
         // Channel counts that are not a multiple of 16: trim into a channel-padded copy
@@ -314,7 +319,7 @@ extern "C" sparq_status sparq_conv_gemm(const uint8_t* x, const void* packed_w, 
         q.x = xin;
         q.wpk = static_cast<const uint8_t*>(packed_w) + g.w_off;
         q.colsum = static_cast<const int32_t*>(packed_w);
-        q.acc = acc; q.scale = scale; q.out = out;
+        q.acc = acc; q.scale = scale; q.out = out; q.out_u8 = y;
         q.x_bytes = (uint32_t)x_bytes;
         q.w_bytes = (uint32_t)((size_t)g.Kp * g.Np);
         q.N = g.N; q.Np = g.Np; q.C = g.Cp;
@@ -329,9 +334,10 @@ extern "C" sparq_status sparq_conv_gemm(const uint8_t* x, const void* packed_w, 
             int32_t* sum = acc ? acc : reinterpret_cast<int32_t*>(static_cast<uint8_t*>(workspace) + pl.pad_bytes);
             sparq_status st = launch_zero(sum, (size_t)round_up(g.M * g.N * 4, 16), s);
             if (st != SPARQ_OK) return st;
-            q.acc = sum; q.scale = nullptr; q.out = nullptr;
+            q.acc = sum; q.scale = nullptr; q.out = nullptr; q.out_u8 = nullptr;
             st = pl.variant->fn_split(kind, q, pl.npix, s);
             if (st == SPARQ_OK && out) st = sparq_dequant(sum, scale, out, g.M, g.N, stream);
+            if (st == SPARQ_OK && y) st = sparq_requant(sum, scale, y, g.M, g.N, stream);
             if (st != SPARQ_EUNSUPPORTED) return st;
         } else {
             const PatchLauncher fn = pl.ws ? pl.variant->fn_ws : pl.variant->fn;
@@ -347,6 +353,7 @@ extern "C" sparq_status sparq_conv_gemm(const uint8_t* x, const void* packed_w, 
     p.acc = acc;
     p.scale = scale;
     p.out = out;
+    p.out_u8 = y;
     p.M = g.M;
     p.x_bytes = (uint32_t)x_bytes;
     p.N = g.N; p.Np = g.Np; p.Kk = g.Kk; p.nkb = g.Kp / kStepK; p.scale_n = g.N;
@@ -356,5 +363,21 @@ extern "C" sparq_status sparq_conv_gemm(const uint8_t* x, const void* packed_w, 
     p.rcp_kw = 1.0f / (float)g.KW;
     p.luts = make_luts(mode->window_bits, mode->shift_mask);
 
-    return pick_tile(g)(kind, p, s);
+    return pick_tile(g, y != nullptr)(kind, p, s);
+}
+
+}  // namespace
+
+extern "C" sparq_status sparq_conv_gemm(const uint8_t* x, const void* packed_w, const sparq_conv_desc* desc,
+                                        const sparq_mode* mode, int32_t* acc, const float* scale, float* out,
+                                        void* workspace, size_t workspace_bytes, void* stream) {
+    if (!acc && !out) return SPARQ_EINVAL;
+    return conv_launch(x, packed_w, desc, mode, acc, scale, out, nullptr, workspace, workspace_bytes, stream);
+}
+
+extern "C" sparq_status sparq_conv_gemm_u8(const uint8_t* x, const void* packed_w, const sparq_conv_desc* desc,
+                                           const sparq_mode* mode, const float* factor, uint8_t* y,
+                                           void* workspace, size_t workspace_bytes, void* stream) {
+    if (!factor || !y) return SPARQ_EINVAL;
+    return conv_launch(x, packed_w, desc, mode, nullptr, factor, nullptr, y, workspace, workspace_bytes, stream);
 }

@@ -33,6 +33,7 @@ struct GemmParams {
     int32_t* acc;            // [M][N] or null
     const float* scale;      // [N] or null
     float* out;              // [M][N] or null
+    uint8_t* out_u8;         // [M][N] requantised output or null (then it is the only output; scale holds its factors)
     int64_t M;
     uint32_t x_bytes;
     int N, Np, Kk, nkb;
@@ -71,6 +72,8 @@ struct TileCfg {
     static constexpr int kUnroll = lcm3(2, PA, PB);             // main-loop unroll: every ring index compile-time
     // resident workgroups per CU the register budget is set for (0: two with small accumulators, else one)
     static constexpr int kWgPerCu = WPC ? WPC : ((kFM * kFN * 16 <= 64) ? 2 : 1);
+    // the widest tile has no registers to spare for a third epilogue copy: no requantised-byte output
+    static constexpr bool kByteOutput = kFM * kFN * 16 <= 128;
     static_assert(TM % (32 * WGM) == 0 && TN % (32 * WGN) == 0, "tile must split into 32x32 fragments");
     static_assert((TM * 4) % kThreads == 0, "activation loads must divide evenly");
     static_assert(PA >= 1 && PA <= 4 && PB >= 1 && PB <= 4, "prefetch depth");
@@ -294,15 +297,17 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
         {
             const int64_t left = p.M - m0;
             const int rows = left < Cfg::kTM ? (int)left : Cfg::kTM;
-            const int pitch = p.N * 4;
-            const int tile_bytes = rows * pitch;
-            const float* scale_or_dummy = p.out ? p.scale : reinterpret_cast<const float*>(p.colsum);
-            auto store_tile = [&](auto acc_, auto out_) __attribute__((always_inline)) {
-                constexpr bool kAcc = decltype(acc_)::value, kOut = decltype(out_)::value;
+            const float* scale_or_dummy = (p.out || p.out_u8) ? p.scale : reinterpret_cast<const float*>(p.colsum);
+            auto store_tile = [&](auto acc_, auto out_, auto u8_) __attribute__((always_inline)) {
+                constexpr bool kAcc = decltype(acc_)::value, kOut = decltype(out_)::value, kU8 = decltype(u8_)::value;
+                constexpr int kElem = kU8 ? 1 : 4;                 // bytes per stored result
+                const int pitch = p.N * kElem;
+                const int tile_bytes = rows * pitch;
                 const __amdgpu_buffer_rsrc_t arsrc = __builtin_amdgcn_make_buffer_rsrc(
                     kAcc ? (void*)(p.acc + m0 * p.N) : nullptr, 0, kAcc ? tile_bytes : 0, 0x00020000);
                 const __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc(
-                    kOut ? (void*)(p.out + m0 * p.N) : nullptr, 0, kOut ? tile_bytes : 0, 0x00020000);
+                    kOut ? (void*)(p.out + m0 * p.N) : kU8 ? (void*)(p.out_u8 + m0 * p.N) : nullptr, 0,
+                    (kOut || kU8) ? tile_bytes : 0, 0x00020000);
 #pragma unroll
                 for (int j = 0; j < FN; ++j) {
                     const int n = n0 + wn * Cfg::kWTN + j * 32 + l32;
@@ -310,8 +315,8 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
                     // both constants are loaded on every path (a load under a condition makes the
                     // compiler put a full memory wait in front of every store below)
                     int32_t corr = 128 * p.colsum[nc];
-                    float sc = scale_or_dummy[kOut ? nc % p.scale_n : nc];
-                    const uint32_t lane_off = n < p.N ? (uint32_t)((wm * Cfg::kWTM + 4 * lhi) * pitch + n * 4) : kInvalidOffset;
+                    float sc = scale_or_dummy[(kOut || kU8) ? nc % p.scale_n : nc];
+                    const uint32_t lane_off = n < p.N ? (uint32_t)((wm * Cfg::kWTM + 4 * lhi) * pitch + n * kElem) : kInvalidOffset;
                     asm volatile("" : "+v"(corr), "+v"(sc));
 #pragma unroll
                     for (int i = 0; i < FM; ++i)
@@ -323,12 +328,20 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
                             if constexpr (kAcc) __builtin_amdgcn_raw_buffer_store_b32(r, arsrc, off, 0, 0);
                             if constexpr (kOut)
                                 __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, __fmul_rn((float)r, sc)), orsrc, off, 0, 0);
+                            if constexpr (kU8) {
+                                // requantised output: round to nearest even in fp32, clamp to [0, 255]
+                                const float f = __builtin_rintf(__fmul_rn((float)r, sc));
+                                const unsigned q = (unsigned)__builtin_fminf(__builtin_fmaxf(f, 0.0f), 255.0f);
+                                __builtin_amdgcn_raw_buffer_store_b8((unsigned char)q, orsrc, off, 0, 0);
+                            }
                         }
                 }
             };
-            if (p.acc && p.out) store_tile(std::true_type{}, std::true_type{});
-            else if (p.out) store_tile(std::false_type{}, std::true_type{});
-            else store_tile(std::true_type{}, std::false_type{});
+            if (Cfg::kByteOutput && p.out_u8) {
+                if constexpr (Cfg::kByteOutput) store_tile(std::false_type{}, std::false_type{}, std::true_type{});
+            } else if (p.acc && p.out) store_tile(std::true_type{}, std::true_type{}, std::false_type{});
+            else if (p.out) store_tile(std::false_type{}, std::true_type{}, std::false_type{});
+            else store_tile(std::true_type{}, std::false_type{}, std::false_type{});
         }
     }   // tile loop
 }
@@ -343,6 +356,7 @@ sparq_status launch_cfg(const GemmParams& p, hipStream_t s) {
             return SPARQ_ELAUNCH;
         attr_set = true;
     }
+    if (p.out_u8 && !Cfg::kByteOutput) return SPARQ_EUNSUPPORTED;
     GemmParams q = p;
     q.tiles_m = (int)((p.M + Cfg::kTM - 1) / Cfg::kTM);
     q.tiles_n = (p.N + Cfg::kTN - 1) / Cfg::kTN;

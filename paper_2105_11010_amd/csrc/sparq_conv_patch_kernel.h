@@ -41,6 +41,7 @@ struct PatchParams {
     int32_t* acc;            // [M][N] or null
     const float* scale;      // [N] or null
     float* out;              // [M][N] or null
+    uint8_t* out_u8;         // [M][N] requantised output or null (then it is the only output; scale holds its factors)
     uint32_t x_bytes, w_bytes;
     int N, Np, C;
     int ncb;                 // channel blocks (units) per work item
@@ -404,7 +405,7 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
             const int64_t m0 = (int64_t)c_tm * kPatchTM;
             const int n0 = (c_tn >> p.split_log2) * TN;
             const int corr_mul = (c_tn & split_mask) == 0 ? 128 : 0;       // only the first split adds the offset term
-            const float* scale_or_dummy = p.out ? p.scale : reinterpret_cast<const float*>(p.colsum);
+            const float* scale_or_dummy = (p.out || p.out_u8) ? p.scale : reinterpret_cast<const float*>(p.colsum);
             if constexpr (Cfg::kSplitK) {
                 // partial sums of a split reduction: int32 adds commute, the result is exact
 #pragma unroll
@@ -430,9 +431,6 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
                 // past N fall outside the buffer's range and are dropped by the hardware (no per-row
                 // branches, no 64-bit address arithmetic).  One copy per combination of outputs, chosen per tile.
                 const int rows = g.M - (int)m0 < kPatchTM ? g.M - (int)m0 : kPatchTM;
-                const int pitch = p.N * 4;
-                const int tile_bytes = rows * pitch;
-                uint32_t lane_off[FN];
                 int32_t corr[FN];
                 float sc[FN];
 #pragma unroll
@@ -443,16 +441,25 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
                     // the compiler put a full memory wait in front of every store below)
                     corr[j] = p.colsum[nc] * corr_mul;
                     sc[j] = scale_or_dummy[nc];
-                    lane_off[j] = n < p.N ? (uint32_t)((wm * Cfg::kWTM + 4 * lhi) * pitch + n * 4) : 0x80000000u;
                 }
 #pragma unroll
                 for (int j = 0; j < FN; ++j) asm volatile("" : "+v"(corr[j]), "+v"(sc[j]));   // loads have landed from here on
-                auto store_tile = [&](auto acc_, auto out_) __attribute__((always_inline)) {
-                    constexpr bool kAcc = decltype(acc_)::value, kOut = decltype(out_)::value;
+                auto store_tile = [&](auto acc_, auto out_, auto u8_) __attribute__((always_inline)) {
+                    constexpr bool kAcc = decltype(acc_)::value, kOut = decltype(out_)::value, kU8 = decltype(u8_)::value;
+                    constexpr int kElem = kU8 ? 1 : 4;                 // bytes per stored result
+                    const int pitch = p.N * kElem;
+                    const int tile_bytes = rows * pitch;
                     const __amdgpu_buffer_rsrc_t arsrc = __builtin_amdgcn_make_buffer_rsrc(
                         kAcc ? (void*)(p.acc + m0 * p.N) : nullptr, 0, kAcc ? tile_bytes : 0, 0x00020000);
                     const __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc(
-                        kOut ? (void*)(p.out + m0 * p.N) : nullptr, 0, kOut ? tile_bytes : 0, 0x00020000);
+                        kOut ? (void*)(p.out + m0 * p.N) : kU8 ? (void*)(p.out_u8 + m0 * p.N) : nullptr, 0,
+                        (kOut || kU8) ? tile_bytes : 0, 0x00020000);
+                    uint32_t lane_off[FN];
+#pragma unroll
+                    for (int j = 0; j < FN; ++j) {
+                        const int n = n0 + wn * Cfg::kWTN + j * 32 + l32;
+                        lane_off[j] = n < p.N ? (uint32_t)((wm * Cfg::kWTM + 4 * lhi) * pitch + n * kElem) : 0x80000000u;
+                    }
 #pragma unroll
                     for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -465,12 +472,19 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
                                 if constexpr (kAcc) __builtin_amdgcn_raw_buffer_store_b32(r, arsrc, off, 0, 0);
                                 if constexpr (kOut)
                                     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, __fmul_rn((float)r, sc[j])), orsrc, off, 0, 0);
+                                if constexpr (kU8) {
+                                    // requantised output: round to nearest even in fp32, clamp to [0, 255]
+                                    const float f = __builtin_rintf(__fmul_rn((float)r, sc[j]));
+                                    const unsigned q = (unsigned)__builtin_fminf(__builtin_fmaxf(f, 0.0f), 255.0f);
+                                    __builtin_amdgcn_raw_buffer_store_b8((unsigned char)q, orsrc, off, 0, 0);
+                                }
                             }
                         }
                 };
-                if (p.acc && p.out) store_tile(std::true_type{}, std::true_type{});
-                else if (p.out) store_tile(std::false_type{}, std::true_type{});
-                else store_tile(std::true_type{}, std::false_type{});
+                if (p.out_u8) store_tile(std::false_type{}, std::false_type{}, std::true_type{});
+                else if (p.acc && p.out) store_tile(std::true_type{}, std::true_type{}, std::false_type{});
+                else if (p.out) store_tile(std::false_type{}, std::true_type{}, std::false_type{});
+                else store_tile(std::true_type{}, std::false_type{}, std::false_type{});
             }
             zero_acc();
         }

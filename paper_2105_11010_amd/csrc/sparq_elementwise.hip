@@ -150,6 +150,32 @@ __global__ __launch_bounds__(kEwThreads) void dequant_scalar_kernel(const int32_
         out[i] = __fmul_rn((float)acc[i], scale[i % N]);
 }
 
+// ---- requantisation to the next layer's unsigned 8-bit activations ------------
+// y = clamp(round_to_nearest_even(acc * factor[n]), 0, 255), the product and the rounding in fp32
+__device__ __forceinline__ uint32_t requant_one(int32_t a, float f) {
+    const float r = __builtin_rintf(__fmul_rn((float)a, f));
+    return (uint32_t)__builtin_fminf(__builtin_fmaxf(r, 0.0f), 255.0f);
+}
+
+__global__ __launch_bounds__(kEwThreads) void requant_vec_kernel(const int4* __restrict__ acc, const float* __restrict__ factor,
+                                                                 uint32_t* __restrict__ y, int64_t n_vec, int N) {
+    // N % 4 == 0: a word of four results never straddles a row
+    const int64_t stride = (int64_t)gridDim.x * kEwThreads;
+    for (int64_t i = (int64_t)blockIdx.x * kEwThreads + threadIdx.x; i < n_vec; i += stride) {
+        const int n = (int)((i * 4) % N);
+        const int4 a = acc[i];
+        const float4 f = *reinterpret_cast<const float4*>(factor + n);
+        y[i] = requant_one(a.x, f.x) | (requant_one(a.y, f.y) << 8) | (requant_one(a.z, f.z) << 16) | (requant_one(a.w, f.w) << 24);
+    }
+}
+
+__global__ __launch_bounds__(kEwThreads) void requant_scalar_kernel(const int32_t* __restrict__ acc, const float* __restrict__ factor,
+                                                                    uint8_t* __restrict__ y, int64_t total, int N) {
+    const int64_t stride = (int64_t)gridDim.x * kEwThreads;
+    for (int64_t i = (int64_t)blockIdx.x * kEwThreads + threadIdx.x; i < total; i += stride)
+        y[i] = (uint8_t)requant_one(acc[i], factor[i % N]);
+}
+
 // ---- weight packing ----------------------------------------------------------
 // packed[w_off + ((kb*4 + kc)*Np + n)*16 + j] = w[n][tap][c + j]  with  k = kb*64 + kc*16 = tap*Cp + c
 __global__ __launch_bounds__(kEwThreads) void pack_weights_kernel(const int8_t* __restrict__ w, uint4* __restrict__ dst,
@@ -267,6 +293,24 @@ extern "C" sparq_status sparq_dequant(const int32_t* acc, const float* scale, fl
             reinterpret_cast<const int4*>(acc), scale, reinterpret_cast<float4*>(out), n_vec, N);
     } else {
         dequant_scalar_kernel<<<ew_grid(total, kEwThreads * 4), kEwThreads, 0, s>>>(acc, scale, out, total, N);
+    }
+    return launch_status();
+}
+
+extern "C" sparq_status sparq_requant(const int32_t* acc, const float* factor, uint8_t* y, int64_t M, int32_t N,
+                                      void* stream) {
+    if (M < 0 || N <= 0) return SPARQ_EINVAL;
+    if (M == 0) return SPARQ_OK;
+    if (!acc || !factor || !y) return SPARQ_EINVAL;
+    if (M > (INT64_MAX / 8) / N) return SPARQ_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t total = M * N;
+    if (N % 4 == 0 && aligned(acc, 16) && aligned(y, 4) && aligned(factor, 16)) {
+        const int64_t n_vec = total / 4;
+        requant_vec_kernel<<<ew_grid(n_vec, kEwThreads * 4), kEwThreads, 0, s>>>(
+            reinterpret_cast<const int4*>(acc), factor, reinterpret_cast<uint32_t*>(y), n_vec, N);
+    } else {
+        requant_scalar_kernel<<<ew_grid(total, kEwThreads * 4), kEwThreads, 0, s>>>(acc, factor, y, total, N);
     }
     return launch_status();
 }

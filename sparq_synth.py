@@ -133,6 +133,13 @@ def gen_scales(n: int, rng: np.random.Generator) -> np.ndarray:
     return rng.uniform(1e-3, 1e-2, size=n).astype(np.float32)
 
 
+def gen_requant(layer: "ConvLayer", rng: np.random.Generator) -> np.ndarray:
+    """Per-output-channel requantisation factors (input scale * weight scale / output scale) sized so that the
+    requantised results of the synthetic tensors use the whole unsigned 8-bit range: about half of them clamp
+    at 0, a few per cent at 255 (accumulator spread ~ 2000 * sqrt(K) for these activations and weights)."""
+    return (rng.uniform(0.7, 1.3, size=layer.N) * (0.044 / np.sqrt(layer.K))).astype(np.float32)
+
+
 def gen_layer(config: int, layer: ConvLayer):
     """(x uint8 NHWC, w int8 [N,KH,KW,C], scale fp32 [N]) for one layer."""
     rng = rng_for(config, layer.index)

@@ -14,7 +14,7 @@ HEADER = os.path.join(ROOT, "include", "sparq.h")
 def declared_symbols():
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(sparq_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(sparq_[a-z0-9_]+)\s*\(", text)))
 
 
 @pytest.fixture(scope="module")
@@ -26,8 +26,8 @@ def lib():
 
 
 def test_header_declares_the_boundary():
-    assert declared_symbols() == ["sparq_conv_gemm", "sparq_conv_plan", "sparq_dequant", "sparq_pack_weights", "sparq_packed_bytes",
-                                  "sparq_strerror", "sparq_trim", "sparq_workspace_bytes"]
+    assert declared_symbols() == ["sparq_conv_gemm", "sparq_conv_gemm_u8", "sparq_conv_plan", "sparq_dequant", "sparq_pack_weights",
+                                  "sparq_packed_bytes", "sparq_requant", "sparq_strerror", "sparq_trim", "sparq_workspace_bytes"]
 
 
 def test_every_declared_symbol_is_exported(lib):
@@ -92,6 +92,9 @@ def test_argument_validation_returns_codes(lib):
     assert lib.sparq_trim(fake, fake, ctypes.c_int64(0), 16, ctypes.byref(m), None) == 0     # empty: nothing to do
     assert lib.sparq_dequant(None, fake, fake, ctypes.c_int64(1), 4, None) == EINVAL
     assert lib.sparq_dequant(fake, fake, fake, ctypes.c_int64(1), 0, None) == EINVAL
+    assert lib.sparq_requant(None, fake, fake, ctypes.c_int64(1), 4, None) == EINVAL
+    assert lib.sparq_requant(fake, fake, fake, ctypes.c_int64(-1), 4, None) == EINVAL
+    assert lib.sparq_requant(fake, fake, fake, ctypes.c_int64(0), 4, None) == 0
     assert lib.sparq_dequant(fake, fake, fake, ctypes.c_int64(0), 4, None) == 0
     assert lib.sparq_pack_weights(None, ctypes.byref(d), fake, ctypes.c_size_t(1 << 20), None) == EINVAL
     assert lib.sparq_pack_weights(fake, ctypes.byref(d), ctypes.c_void_p(0x1010), ctypes.c_size_t(1 << 20), None) == EINVAL

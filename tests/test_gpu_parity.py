@@ -106,6 +106,46 @@ def test_dequant(sq, oracle, M, N):
     assert np.all(err <= 1e-6 * np.abs(ref))
 
 
+# ------------------------------------------------------------- requant ------
+
+@pytest.mark.parametrize("M,N", [(1, 1), (37, 19), (513, 64), (1000, 160), (0, 8)])
+def test_requant(sq, oracle, M, N):
+    """The standalone requantisation pass: bit-exact bytes, ties and both clamps included."""
+    rng = S.rng_for(8, 400 + N)
+    acc = rng.integers(-60000, 200000, size=(M, N), dtype=np.int64).astype(np.int32)
+    if M:
+        acc[0, 0] = 5                       # 2.5 with factor 0.5: the tie
+    f = rng.uniform(5e-4, 3e-3, size=N).astype(np.float32)
+    f[0] = 0.5
+    y = torch.full((M, N), 7, dtype=torch.uint8, device="cuda:0")
+    sq.sparq_requant(dev(acc), dev(f), y)
+    torch.cuda.synchronize()
+    assert np.array_equal(y.cpu().numpy(), oracle.requant(acc, f))
+
+
+def run_conv_u8(sq, x, w, f, layer, mode):
+    d = sq.conv_desc(layer.B, layer.H, layer.W, layer.C, layer.N, layer.KH, layer.KW, layer.stride, layer.pad)
+    m = sq.mode(*mode.astuple())
+    packed = torch.empty(sq.sparq_packed_bytes(d), dtype=torch.uint8, device="cuda:0")
+    sq.sparq_pack_weights(dev(w), d, packed)
+    wsb = sq.sparq_workspace_bytes(d, m)
+    ws = torch.empty(wsb, dtype=torch.uint8, device="cuda:0") if wsb else None
+    y = torch.full((layer.M, layer.N), 7, dtype=torch.uint8, device="cuda:0")
+    sq.sparq_conv_gemm_u8(dev(x), packed, d, m, dev(f), y, workspace=ws)
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+def check_layer_u8(sq, oracle, layer, mode, seed_cfg=8):
+    """Requantised uint8 output of the fused convolution: every byte equals the oracle's."""
+    x, w, _ = S.gen_layer(seed_cfg, layer)
+    f = S.gen_requant(layer, S.rng_for(seed_cfg, 900 + layer.index))
+    y = run_conv_u8(sq, x, w, f, layer, mode)
+    ref = oracle.conv_gemm_u8(x, w, f, layer.stride, layer.pad, **mode.kwargs())
+    assert np.array_equal(y, ref), f"{layer.name} {mode.label}: uint8 mismatch"
+    assert (ref == 0).any() and ref.max() > 60, "degenerate test case"
+
+
 # ---------------------------------------------------------- conv / gemm -----
 
 def test_config0_full(sq, oracle):
@@ -195,6 +235,44 @@ PATCH_SHAPES = [
 @pytest.mark.parametrize("mode", [S.Mode(4, S.OPT5, 1, 1), S.Mode(3, S.OPT6_3B, 0, 1)], ids=lambda m: m.label)
 def test_conv_patch_shapes(sq, oracle, layer, mode, path):
     check_layer(sq, oracle, layer, mode, seed_cfg=9)
+
+
+@pytest.mark.parametrize("layer", SHAPES + PATCH_SHAPES, ids=lambda l: l.name)
+def test_conv_u8_shapes(sq, oracle, layer, path):
+    """The requantised-output entry point on every shape and through every kernel form."""
+    check_layer_u8(sq, oracle, layer, S.Mode(4, S.OPT5, 1, 1), seed_cfg=9)
+
+
+@pytest.mark.parametrize("tile", ["128x128", "128x256", "128x512"])
+def test_conv_u8_gather_tiles(sq, oracle, monkeypatch, tile):
+    """Gather-kernel tiles with the byte output (the widest tile has none: the library picks the next one)."""
+    monkeypatch.setenv("SPARQ_PATH", "gather")
+    monkeypatch.setenv("SPARQ_TILE", tile)
+    check_layer_u8(sq, oracle, S.ConvLayer("u8_tiles", 1, 9, 31, 96, 520, 3, 3, (1, 1), (1, 1)), S.Mode(4, S.OPT3, 1, 1), seed_cfg=9)
+
+
+@pytest.mark.parametrize("split", ["1", "2"])
+def test_conv_u8_split_reduction(sq, oracle, monkeypatch, split):
+    """Split reductions sum int32 partial results in the workspace; the bytes come from a requantisation pass."""
+    monkeypatch.setenv("SPARQ_PATH", "patch")
+    monkeypatch.setenv("SPARQ_PATCH_TN", "128")
+    monkeypatch.setenv("SPARQ_SPLIT", split)
+    check_layer_u8(sq, oracle, S.ConvLayer("u8_split", 3, 7, 7, 512, 130, 3, 3, (1, 1), (1, 1)), S.Mode(4, S.OPT5, 1, 1), seed_cfg=9)
+
+
+def test_conv_u8_chain(sq, oracle):
+    """Two layers chained on the device: the first layer's bytes are the second layer's NHWC input."""
+    l1 = S.ConvLayer("chain1", 2, 12, 12, 64, 96, 3, 3, (1, 1), (1, 1))
+    l2 = S.ConvLayer("chain2", 2, 12, 12, 96, 40, 1, 1, index=1)
+    mode = S.Mode(4, S.OPT5, 1, 1)
+    x, w1, _ = S.gen_layer(9, l1)
+    _, w2, _ = S.gen_layer(9, l2)
+    f1, f2 = S.gen_requant(l1, S.rng_for(9, 950)), S.gen_requant(l2, S.rng_for(9, 951))
+    y1 = run_conv_u8(sq, x, w1, f1, l1, mode)
+    y2 = run_conv_u8(sq, y1.reshape(l2.x_shape()), w2, f2, l2, mode)
+    r1 = oracle.conv_gemm_u8(x, w1, f1, l1.stride, l1.pad, **mode.kwargs())
+    r2 = oracle.conv_gemm_u8(r1.reshape(l2.x_shape()), w2, f2, l2.stride, l2.pad, **mode.kwargs())
+    assert np.array_equal(y1, r1) and np.array_equal(y2, r2)
 
 
 @pytest.mark.parametrize("tn", ["64", "128", "256"])

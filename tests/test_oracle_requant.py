@@ -97,9 +97,7 @@ def test_half_way_products_that_need_the_fp32_rounding_first():
     got = oracle.requant(np.array([[(1 << 24) + 1, 1 << 24, (1 << 24) + 2]], dtype=np.int32),
                          np.full(3, 2.5 * 2.0 ** -24, dtype=np.float32))
     assert got.tolist() == [[2, 2, 3]]
-    # the product is rounded to fp32 before the integer rounding: 3 * (0.5 + 2^-25) = 1.5000000894 is 1.5 in fp32
-    # only if the factor itself is representable: 0.5 + 2^-24 is (24 bits), 3 * that = 1.50000018 -> fp32 1.5000002 -> 2;
-    # 12582913 * (2^-23) = 1.50000012 stays above the tie -> 2, while 12582912 * 2^-23 = 1.5 -> 2 and 4194304 * 2^-23 = 0.5 -> 0
+    # 2^-23 is a power of two, so these products are exact: 1.50000012 -> 2, 1.5 (tie) -> 2, 0.5 (tie) -> 0, 0.50000012 -> 1
     got = oracle.requant(np.array([[12582913, 12582912, 4194304, 4194305]], dtype=np.int32), np.full(4, 2.0 ** -23, dtype=np.float32))
     assert got.tolist() == [[2, 2, 0, 1]]
     # 2^25 + 2 -> fp32 keeps it (even significand), 2^25 + 6 rounds to 2^25 + 8
