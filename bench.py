@@ -52,6 +52,9 @@ def parse_args():
     ap.add_argument("--zf", type=float, default=None, help="cfg3 only: zero fraction override")
     ap.add_argument("--rows", type=int, default=65536, help="cfg3 only: M")
     ap.add_argument("--batch", type=int, default=None, help="cfg1/2/4: batch override")
+    ap.add_argument("--output", default="fp32", choices=["fp32", "u8"],
+                    help="fp32: fused per-channel dequantisation (the headline form); u8: results requantised to the next "
+                         "layer's unsigned 8-bit activations (sparq_conv_gemm_u8)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-layer", action="store_true", help="print a per-layer table on stderr")
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary figures of the default run")
@@ -98,7 +101,7 @@ def build_workload(args):
     raise SystemExit(f"unknown workload {wl}")
 
 
-def prepare(sq, S, torch, dev, cfg_id, layers, keep_host=False):
+def prepare(sq, S, torch, dev, cfg_id, layers, keep_host=False, outputs=("fp32",)):
     """Generate every layer's tensors, upload them and pack the weights (all before any timing)."""
     items = []
     for layer in layers:
@@ -112,31 +115,42 @@ def prepare(sq, S, torch, dev, cfg_id, layers, keep_host=False):
         sq.sparq_pack_weights(wd, d, packed)
         wsb = sq.sparq_workspace_bytes(d, m)
         ws = torch.empty(wsb, dtype=torch.uint8, device=dev) if wsb else None
-        out = torch.empty((layer.M, layer.N), dtype=torch.float32, device=dev)
-        items.append(dict(layer=layer, d=d, m=m, x=xd, sc=sd, packed=packed, ws=ws, out=out,
+        out = torch.empty((layer.M, layer.N), dtype=torch.float32, device=dev) if "fp32" in outputs else None
+        y = rq = None
+        if "u8" in outputs:
+            y = torch.empty((layer.M, layer.N), dtype=torch.uint8, device=dev)
+            rq = torch.from_numpy(S.gen_requant(layer, S.rng_for(cfg_id, 900 + layer.index))).to(dev)
+        items.append(dict(layer=layer, d=d, m=m, x=xd, sc=sd, packed=packed, ws=ws, out=out, y=y, rq=rq,
                           host=(x, w, sc) if keep_host else None))
         del wd
     torch.cuda.synchronize()
     return items
 
 
-def run_step(sq, items):
+def run_layer(sq, it, output="fp32"):
+    if output == "u8":
+        sq.sparq_conv_gemm_u8(it["x"], it["packed"], it["d"], it["m"], it["rq"], it["y"], workspace=it["ws"])
+    else:
+        sq.sparq_conv_gemm(it["x"], it["packed"], it["d"], it["m"], acc=None, scale=it["sc"], out=it["out"],
+                           workspace=it["ws"])
+
+
+def run_step(sq, items, output="fp32"):
     for it in items:
         for _ in range(it["layer"].repeat):
-            sq.sparq_conv_gemm(it["x"], it["packed"], it["d"], it["m"], acc=None, scale=it["sc"], out=it["out"],
-                               workspace=it["ws"])
+            run_layer(sq, it, output)
 
 
-def time_steps(sq, torch, items, warmup, steps):
+def time_steps(sq, torch, items, warmup, steps, output="fp32"):
     """(device ms per step from HIP events on the launch stream, host wall ms per step)."""
     for _ in range(warmup):
-        run_step(sq, items)
+        run_step(sq, items, output)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     e0.record()
     for _ in range(steps):
-        run_step(sq, items)
+        run_step(sq, items, output)
     e1.record()
     torch.cuda.synchronize()
     return e0.elapsed_time(e1) / steps, (time.perf_counter() - t0) * 1e3 / steps
@@ -212,10 +226,10 @@ def main():
 
     # ---- inputs resident in HBM before anything is timed ----
     t_gen = time.time()
-    items = prepare(sq, S, torch, dev, cfg_id, layers, keep_host=len(layers) == 1)
+    items = prepare(sq, S, torch, dev, cfg_id, layers, keep_host=len(layers) == 1, outputs=(args.output,))
     print(f"[bench] inputs generated and uploaded in {time.time() - t_gen:.1f}s", file=sys.stderr, flush=True)
 
-    ms_per_step, wall_ms = time_steps(sq, torch, items, args.warmup, args.steps)
+    ms_per_step, wall_ms = time_steps(sq, torch, items, args.warmup, args.steps, args.output)
     total_ops = S.total_ops(layers)
     tops = total_ops / (ms_per_step * 1e-3) / 1e12
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -224,23 +238,23 @@ def main():
     dom = max(items, key=lambda it: it["layer"].ops * it["layer"].repeat)
     reps = max(5, args.steps)
     for _ in range(2):
-        sq.sparq_conv_gemm(dom["x"], dom["packed"], dom["d"], dom["m"], scale=dom["sc"], out=dom["out"], workspace=dom["ws"])
+        run_layer(sq, dom, args.output)
     torch.cuda.synchronize()
     e0.record()
     for _ in range(reps):
-        sq.sparq_conv_gemm(dom["x"], dom["packed"], dom["d"], dom["m"], scale=dom["sc"], out=dom["out"], workspace=dom["ws"])
+        run_layer(sq, dom, args.output)
     e1.record()
     torch.cuda.synchronize()
     dom_ms = e0.elapsed_time(e1) / reps
     dom_tops = dom["layer"].ops / (dom_ms * 1e-3) / 1e12
     tr = MEASURED_TRAFFIC.get(args.workload) if (args.rows == 65536 and args.mask is None and args.round is None
-                                                 and args.pair is None and args.zf is None) else None
+                                                 and args.pair is None and args.zf is None and args.output == "fp32") else None
     x_b, w_b = dom["x"].numel(), dom["layer"].K * dom["layer"].N
     roofline = {"bound": "mfma", "achieved": round(dom_tops, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
                 "frac": round(dom_tops / PEAK_INT8_TOPS, 4),
                 "traffic": (tr["fetch_bytes"] + tr["write_bytes"]) if tr else None,
                 "traffic_detail": tr,
-                "algorithmic_bytes": x_b + w_b + 4 * dom["layer"].M * dom["layer"].N,
+                "algorithmic_bytes": x_b + w_b + (1 if args.output == "u8" else 4) * dom["layer"].M * dom["layer"].N,
                 "kernel": sq.sparq_conv_plan(dom["d"], dom["m"]), "layer": dom["layer"].name, "ms_per_launch": round(dom_ms, 4),
                 "ops_per_launch": dom["layer"].ops}
 
@@ -258,28 +272,29 @@ def main():
     trim_ms = e0.elapsed_time(e1) / reps
     trim_gbps = 2 * xin.numel() / (trim_ms * 1e-3) / 1e9
     del y
-    acc = torch.randint(-2 ** 24, 2 ** 24, dom["out"].shape, dtype=torch.int32, device=dev)
+    acc = torch.randint(-2 ** 24, 2 ** 24, (dom["layer"].M, dom["layer"].N), dtype=torch.int32, device=dev)
+    deq_out = dom["out"] if dom["out"] is not None else torch.empty(acc.shape, dtype=torch.float32, device=dev)
     for _ in range(2):
-        sq.sparq_dequant(acc, dom["sc"], dom["out"])
+        sq.sparq_dequant(acc, dom["sc"], deq_out)
     torch.cuda.synchronize()
     e0.record()
     for _ in range(reps):
-        sq.sparq_dequant(acc, dom["sc"], dom["out"])
+        sq.sparq_dequant(acc, dom["sc"], deq_out)
     e1.record()
     torch.cuda.synchronize()
     deq_ms = e0.elapsed_time(e1) / reps
     deq_gbps = 8 * acc.numel() / (deq_ms * 1e-3) / 1e9
-    del acc
+    del acc, deq_out
 
     if args.per_layer:
         print(f"{'layer':28s} {'M':>8s} {'K':>6s} {'N':>5s} {'rep':>3s} {'ms':>9s} {'TOPS':>8s}", file=sys.stderr)
         for it in items:
             L = it["layer"]
-            sq.sparq_conv_gemm(it["x"], it["packed"], it["d"], it["m"], scale=it["sc"], out=it["out"], workspace=it["ws"])
+            run_layer(sq, it, args.output)
             torch.cuda.synchronize()
             e0.record()
             for _ in range(10):
-                sq.sparq_conv_gemm(it["x"], it["packed"], it["d"], it["m"], scale=it["sc"], out=it["out"], workspace=it["ws"])
+                run_layer(sq, it, args.output)
             e1.record()
             torch.cuda.synchronize()
             ms = e0.elapsed_time(e1) / 10
@@ -295,10 +310,15 @@ def main():
         for wl in ("cfg3", "cfg1", "cfg4"):
             a2 = argparse.Namespace(**{**vars(args), "workload": wl})
             c2, l2, n2 = build_workload(a2)
-            it2 = prepare(sq, S, torch, dev, c2, l2)
+            it2 = prepare(sq, S, torch, dev, c2, l2, outputs=("fp32", "u8"))
             ms2, _ = time_steps(sq, torch, it2, args.warmup, args.steps)
             also.append({"workload": n2, "value": round(S.total_ops(l2) / ms2 / 1e9, 2), "unit": "TOPS",
                          "ms_per_step": round(ms2, 4), "total_gop": round(S.total_ops(l2) / 1e9, 3)})
+            if wl != "cfg3":
+                # the same table with every result requantised to uint8 (one byte per output instead of four)
+                ms3, _ = time_steps(sq, torch, it2, args.warmup, args.steps, "u8")
+                also.append({"workload": n2 + ", uint8 requantised outputs", "value": round(S.total_ops(l2) / ms3 / 1e9, 2),
+                             "unit": "TOPS", "ms_per_step": round(ms3, 4), "total_gop": round(S.total_ops(l2) / 1e9, 3)})
             del it2
             torch.cuda.empty_cache()
 
@@ -345,7 +365,8 @@ def main():
         "dtype": "int8",
         "data": "synthetic",
         "config": {"workload": wl_name, "layers": sum(l.repeat for l in layers), "total_gop": round(total_ops / 1e9, 3),
-                   "output": "fp32 (fused dequant)", "wall_ms_per_step": round(wall_ms, 4)},
+                   "output": "fp32 (fused dequant)" if args.output == "fp32" else "uint8 (fused requantisation)",
+                   "wall_ms_per_step": round(wall_ms, 4)},
         "pct_int8_mfma_peak": round(100 * tops / PEAK_INT8_TOPS, 2),
         "roofline": roofline,
         "trim": {"GBps": round(trim_gbps, 1), "frac_hbm_peak": round(trim_gbps / PEAK_HBM_GBPS, 4),

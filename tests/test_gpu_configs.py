@@ -1,8 +1,8 @@
 """GPU parity at the benchmark's full sizes: every layer of the five workload tables runs through
 the C ABI exactly as bench.py launches it (full tensors, fused dequantisation); the CPU oracle then
 recomputes a sample of output rows one by one -- first and last tile, image borders, random interior
-rows; 4096 and more rows on the largest layers -- and those must match bit-exactly (int32) and to
-1e-6 relative (fp32)."""
+rows; 4096 and more rows on the largest layers -- and those must match bit-exactly (int32, and the
+requantised uint8 bytes of the second entry point) and to 1e-6 relative (fp32)."""
 from dataclasses import replace
 
 import numpy as np
@@ -63,12 +63,24 @@ def _check_one(sq, oracle, layer, data, n):
     deq = torch.empty_like(out)
     sq.sparq_dequant(acc, sd, deq)
     assert torch.equal(deq, out), f"{layer.name}: fused and standalone dequantisation differ"
+    del out, deq
+    # the requantised-output entry point on the same tensors: its bytes are the requantised accumulators
+    # everywhere (a property at any size), and equal the oracle's on the sampled rows
+    fq = S.gen_requant(layer, S.rng_for(2, 900 + layer.index))
+    fd = torch.from_numpy(fq).to(dev)
+    y = torch.empty((layer.M, layer.N), dtype=torch.uint8, device=dev)
+    sq.sparq_conv_gemm_u8(xd, packed, d, m, fd, y, workspace=ws)
+    y2 = torch.empty_like(y)
+    sq.sparq_requant(acc, fd, y2)
+    assert torch.equal(y, y2), f"{layer.name}: fused and standalone requantisation differ"
+    got_y = y[ridx].cpu().numpy()
     torch.cuda.synchronize()
-    del acc, out, deq, xd
+    del acc, y, y2, xd
     ref_acc, ref_out = oracle.conv_gemm(x, w, layer.stride, layer.pad, scale=sc, rows=rows, **layer.mode.kwargs())
     assert int(got_acc.astype(np.int64).sum()) == int(ref_acc.astype(np.int64).sum()), f"{layer.name}: checksum of sampled rows"
     assert np.array_equal(got_acc, ref_acc), f"{layer.name} {layer.mode.label}: int32 mismatch on sampled rows"
     assert np.all(np.abs(got_out.astype(np.float64) - ref_out) <= 1e-6 * np.abs(ref_out)), f"{layer.name}: fp32 off"
+    assert np.array_equal(got_y, oracle.requant(ref_acc, fq)), f"{layer.name} {layer.mode.label}: uint8 mismatch on sampled rows"
 
 
 # ---- config 1: ResNet-18, batch 32, 3opt floor (first conv plain 8-bit) --------------------------
