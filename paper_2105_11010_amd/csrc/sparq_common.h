@@ -148,6 +148,48 @@ inline ConvGeom folded_view(const ConvGeom& g) {
     return f;
 }
 
+#if defined(__HIPCC__)
+// Requantised result (the arithmetic the byte output is defined by): fp32 product, round to nearest even, clamp.
+__device__ __forceinline__ uint32_t requant_u8(int32_t r, float factor) {
+    const float f = __builtin_rintf(__fmul_rn((float)r, factor));
+    return (uint32_t)__builtin_fminf(__builtin_fmaxf(f, 0.0f), 255.0f);
+}
+
+// 4 x 4 byte transpose inside every group of four neighbouring lanes.  Lane t of a group holds word P_t
+// (byte k = its value for row k); afterwards lane t holds byte t of P_0, P_1, P_2, P_3 (the four lanes'
+// values for row t).  The matrix instruction leaves a lane with four consecutive rows of one channel; after
+// the transpose it has four consecutive channels of one row, i.e. one 32-bit store instead of four byte
+// stores.  sel_a / sel_d depend on the lane only (quad_transpose_selectors).
+// Four requantised results packed into one word (byte k from r[k]): the conversion instruction rounds to
+// nearest even and saturates to [0, 255] by itself.
+__device__ __forceinline__ uint32_t requant_u8x4(int32_t r0, int32_t r1, int32_t r2, int32_t r3, float factor) {
+    uint32_t w = __builtin_amdgcn_cvt_pk_u8_f32(__fmul_rn((float)r0, factor), 0, 0);
+    w = __builtin_amdgcn_cvt_pk_u8_f32(__fmul_rn((float)r1, factor), 1, w);
+    w = __builtin_amdgcn_cvt_pk_u8_f32(__fmul_rn((float)r2, factor), 2, w);
+    return __builtin_amdgcn_cvt_pk_u8_f32(__fmul_rn((float)r3, factor), 3, w);
+}
+
+struct QuadSel { uint32_t a, d; };
+__device__ __forceinline__ QuadSel quad_transpose_selectors(int lane) {
+    const uint32_t t = (uint32_t)lane & 3u;
+    QuadSel q;
+    q.a = t | ((4u + t) << 8);                    // byte t of the low word, byte t of the high word
+    static constexpr uint32_t code[4] = {0u, 1u, 4u, 5u};   // own, lane^1 (low pair); lane^2, lane^3 (high pair)
+    q.d = 0;
+#pragma unroll
+    for (uint32_t s = 0; s < 4; ++s) q.d |= code[s ^ t] << (8 * s);
+    return q;
+}
+__device__ __forceinline__ uint32_t quad_transpose_bytes(uint32_t own, QuadSel sel) {
+    const uint32_t a = (uint32_t)__builtin_amdgcn_mov_dpp((int)own, 0xB1, 0xF, 0xF, true);   // from lane ^ 1
+    const uint32_t b = (uint32_t)__builtin_amdgcn_mov_dpp((int)own, 0x4E, 0xF, 0xF, true);   // from lane ^ 2
+    const uint32_t c = (uint32_t)__builtin_amdgcn_mov_dpp((int)own, 0x1B, 0xF, 0xF, true);   // from lane ^ 3
+    const uint32_t x = __builtin_amdgcn_perm(a, own, sel.a);     // [own.t, a.t, -, -]
+    const uint32_t y = __builtin_amdgcn_perm(c, b, sel.a);       // [b.t, c.t, -, -]
+    return __builtin_amdgcn_perm(y, x, sel.d);
+}
+#endif
+
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 inline sparq_status launch_status() { return hipGetLastError() == hipSuccess ? SPARQ_OK : SPARQ_ELAUNCH; }

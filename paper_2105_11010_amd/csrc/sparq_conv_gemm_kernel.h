@@ -328,17 +328,44 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
                             if constexpr (kAcc) __builtin_amdgcn_raw_buffer_store_b32(r, arsrc, off, 0, 0);
                             if constexpr (kOut)
                                 __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, __fmul_rn((float)r, sc)), orsrc, off, 0, 0);
-                            if constexpr (kU8) {
-                                // requantised output: round to nearest even in fp32, clamp to [0, 255]
-                                const float f = __builtin_rintf(__fmul_rn((float)r, sc));
-                                const unsigned q = (unsigned)__builtin_fminf(__builtin_fmaxf(f, 0.0f), 255.0f);
-                                __builtin_amdgcn_raw_buffer_store_b8((unsigned char)q, orsrc, off, 0, 0);
-                            }
+                            if constexpr (kU8)
+                                __builtin_amdgcn_raw_buffer_store_b8((unsigned char)requant_u8(r, sc), orsrc, off, 0, 0);
+                        }
+                }
+            };
+            // Requantised bytes, N a multiple of 4: the four rows a lane holds of one channel are exchanged
+            // inside groups of four lanes for four channels of one row: one 32-bit store instead of four byte
+            // stores (the byte form is bound by the number of store instructions).
+            auto store_tile_u8_packed = [&]() __attribute__((always_inline)) {
+                const int pitch = p.N;
+                const __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc(
+                    (void*)(p.out_u8 + m0 * p.N), 0, rows * pitch, 0x00020000);
+                const QuadSel qs = quad_transpose_selectors(l32);
+#pragma unroll
+                for (int j = 0; j < FN; ++j) {
+                    const int n = n0 + wn * Cfg::kWTN + j * 32 + l32;
+                    const int nc = n < p.N ? n : 0;
+                    int32_t corr = 128 * p.colsum[nc];
+                    float sc = p.scale[nc % p.scale_n];
+                    const int n4 = n & ~3;
+                    const uint32_t lane_off = n4 < p.N ? (uint32_t)((wm * Cfg::kWTM + 4 * lhi + (l32 & 3)) * pitch + n4) : kInvalidOffset;
+                    asm volatile("" : "+v"(corr), "+v"(sc));
+#pragma unroll
+                    for (int i = 0; i < FM; ++i)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const uint32_t w = requant_u8x4(c[i][j][4 * q] + corr, c[i][j][4 * q + 1] + corr, c[i][j][4 * q + 2] + corr,
+                                                            c[i][j][4 * q + 3] + corr, sc);
+                            __builtin_amdgcn_raw_buffer_store_b32((int)quad_transpose_bytes(w, qs), orsrc,
+                                                                  (int)(lane_off + (uint32_t)((i * 32 + 8 * q) * pitch)), 0, 0);
                         }
                 }
             };
             if (Cfg::kByteOutput && p.out_u8) {
-                if constexpr (Cfg::kByteOutput) store_tile(std::false_type{}, std::false_type{}, std::true_type{});
+                if constexpr (Cfg::kByteOutput) {
+                    if ((p.N & 3) == 0) store_tile_u8_packed();
+                    else store_tile(std::false_type{}, std::false_type{}, std::true_type{});
+                }
             } else if (p.acc && p.out) store_tile(std::true_type{}, std::true_type{}, std::false_type{});
             else if (p.out) store_tile(std::false_type{}, std::true_type{}, std::false_type{});
             else store_tile(std::true_type{}, std::false_type{}, std::false_type{});

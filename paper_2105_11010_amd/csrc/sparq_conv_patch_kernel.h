@@ -472,16 +472,41 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
                                 if constexpr (kAcc) __builtin_amdgcn_raw_buffer_store_b32(r, arsrc, off, 0, 0);
                                 if constexpr (kOut)
                                     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, __fmul_rn((float)r, sc[j])), orsrc, off, 0, 0);
-                                if constexpr (kU8) {
-                                    // requantised output: round to nearest even in fp32, clamp to [0, 255]
-                                    const float f = __builtin_rintf(__fmul_rn((float)r, sc[j]));
-                                    const unsigned q = (unsigned)__builtin_fminf(__builtin_fmaxf(f, 0.0f), 255.0f);
-                                    __builtin_amdgcn_raw_buffer_store_b8((unsigned char)q, orsrc, off, 0, 0);
-                                }
+                                if constexpr (kU8)
+                                    __builtin_amdgcn_raw_buffer_store_b8((unsigned char)requant_u8(r, sc[j]), orsrc, off, 0, 0);
                             }
                         }
                 };
-                if (p.out_u8) store_tile(std::false_type{}, std::false_type{}, std::true_type{});
+                // Requantised bytes, N a multiple of 4: the four rows a lane holds of one channel are exchanged
+                // inside groups of four lanes for four channels of one row: one 32-bit store instead of four
+                // byte stores (the byte form is bound by the number of store instructions).
+                auto store_tile_u8_packed = [&]() __attribute__((always_inline)) {
+                    const int pitch = p.N;
+                    const __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc(
+                        (void*)(p.out_u8 + m0 * p.N), 0, rows * pitch, 0x00020000);
+                    const QuadSel qs = quad_transpose_selectors(l32);
+                    uint32_t lane_off[FN];
+#pragma unroll
+                    for (int j = 0; j < FN; ++j) {
+                        const int n4 = (n0 + wn * Cfg::kWTN + j * 32 + l32) & ~3;
+                        lane_off[j] = n4 < p.N ? (uint32_t)((wm * Cfg::kWTM + 4 * lhi + (l32 & 3)) * pitch + n4) : 0x80000000u;
+                    }
+#pragma unroll
+                    for (int i = 0; i < FM; ++i)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const int row_bytes = (i * 32 + 8 * q) * pitch;
+#pragma unroll
+                            for (int j = 0; j < FN; ++j) {
+                                const uint32_t w = requant_u8x4(c[i][j][4 * q] + corr[j], c[i][j][4 * q + 1] + corr[j], c[i][j][4 * q + 2] + corr[j],
+                                                            c[i][j][4 * q + 3] + corr[j], sc[j]);
+                                __builtin_amdgcn_raw_buffer_store_b32((int)quad_transpose_bytes(w, qs), orsrc,
+                                                                      (int)(lane_off[j] + (uint32_t)row_bytes), 0, 0);
+                            }
+                        }
+                };
+                if (p.out_u8 && (p.N & 3) == 0) store_tile_u8_packed();
+                else if (p.out_u8) store_tile(std::false_type{}, std::false_type{}, std::true_type{});
                 else if (p.acc && p.out) store_tile(std::true_type{}, std::true_type{}, std::false_type{});
                 else if (p.out) store_tile(std::false_type{}, std::true_type{}, std::false_type{});
                 else store_tile(std::true_type{}, std::false_type{}, std::false_type{});

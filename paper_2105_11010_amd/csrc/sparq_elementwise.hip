@@ -152,11 +152,7 @@ __global__ __launch_bounds__(kEwThreads) void dequant_scalar_kernel(const int32_
 
 // ---- requantisation to the next layer's unsigned 8-bit activations ------------
 // y = clamp(round_to_nearest_even(acc * factor[n]), 0, 255), the product and the rounding in fp32
-__device__ __forceinline__ uint32_t requant_one(int32_t a, float f) {
-    const float r = __builtin_rintf(__fmul_rn((float)a, f));
-    return (uint32_t)__builtin_fminf(__builtin_fmaxf(r, 0.0f), 255.0f);
-}
-
+// (requant_u8 and the packing conversion instruction, which rounds and saturates the same way)
 __global__ __launch_bounds__(kEwThreads) void requant_vec_kernel(const int4* __restrict__ acc, const float* __restrict__ factor,
                                                                  uint32_t* __restrict__ y, int64_t n_vec, int N) {
     // N % 4 == 0: a word of four results never straddles a row
@@ -165,7 +161,10 @@ __global__ __launch_bounds__(kEwThreads) void requant_vec_kernel(const int4* __r
         const int n = (int)((i * 4) % N);
         const int4 a = acc[i];
         const float4 f = *reinterpret_cast<const float4*>(factor + n);
-        y[i] = requant_one(a.x, f.x) | (requant_one(a.y, f.y) << 8) | (requant_one(a.z, f.z) << 16) | (requant_one(a.w, f.w) << 24);
+        uint32_t w = __builtin_amdgcn_cvt_pk_u8_f32(__fmul_rn((float)a.x, f.x), 0, 0);
+        w = __builtin_amdgcn_cvt_pk_u8_f32(__fmul_rn((float)a.y, f.y), 1, w);
+        w = __builtin_amdgcn_cvt_pk_u8_f32(__fmul_rn((float)a.z, f.z), 2, w);
+        y[i] = __builtin_amdgcn_cvt_pk_u8_f32(__fmul_rn((float)a.w, f.w), 3, w);
     }
 }
 
@@ -173,7 +172,7 @@ __global__ __launch_bounds__(kEwThreads) void requant_scalar_kernel(const int32_
                                                                     uint8_t* __restrict__ y, int64_t total, int N) {
     const int64_t stride = (int64_t)gridDim.x * kEwThreads;
     for (int64_t i = (int64_t)blockIdx.x * kEwThreads + threadIdx.x; i < total; i += stride)
-        y[i] = (uint8_t)requant_one(acc[i], factor[i % N]);
+        y[i] = (uint8_t)requant_u8(acc[i], factor[i % N]);
 }
 
 // ---- weight packing ----------------------------------------------------------

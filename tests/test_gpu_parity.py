@@ -146,6 +146,20 @@ def check_layer_u8(sq, oracle, layer, mode, seed_cfg=8):
     assert (ref == 0).any() and ref.max() > 60, "degenerate test case"
 
 
+@pytest.mark.parametrize("N", [4, 3])
+def test_requant_every_tie_and_both_clamps(sq, oracle, N):
+    """Factors 0.5 and 0.25 over a run of consecutive accumulators: every second / fourth product is a tie;
+    negative products clamp to 0, large ones to 255 (N = 4: the vector kernel, N = 3: the scalar one)."""
+    acc = np.arange(-600, 600 + 1200 * N, dtype=np.int32)[:1200 * N].reshape(1200, N)
+    f = np.array([0.5, 0.25, 0.5, 0.125][:N], dtype=np.float32)
+    y = torch.full((1200, N), 7, dtype=torch.uint8, device="cuda:0")
+    sq.sparq_requant(dev(acc), dev(f), y)
+    torch.cuda.synchronize()
+    ref = oracle.requant(acc, f)
+    assert np.array_equal(y.cpu().numpy(), ref)
+    assert (ref == 0).any() and (ref == 255).any()
+
+
 # ---------------------------------------------------------- conv / gemm -----
 
 def test_config0_full(sq, oracle):
