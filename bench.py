@@ -58,6 +58,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-layer", action="store_true", help="print a per-layer table on stderr")
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary figures of the default run")
+    ap.add_argument("--sweep-bits", default="4", choices=["4", "low"],
+                    help="cfg3-sweep: the 36 points of the 4-bit option sets (default) or the 24 points of the 3-bit / 6-shift "
+                         "and 2-bit / 7-shift variants")
     ap.add_argument("--sweep-form", default="conv", choices=["conv", "explicit"],
                     help="cfg3-sweep: run the points as the 3x3 convolution (default) or on a materialised A[M,K]")
     return ap.parse_args()
@@ -161,7 +164,7 @@ def sweep(args, sq, S, torch, dev):
     on M=65536, K=4608, N=512; fused conv-GEMM TOPS and standalone trim GB/s for each point."""
     from dataclasses import replace
     points, by_zf = [], {}
-    for mode, zf in S.config3_sweep():
+    for mode, zf in (S.config3_sweep_low() if args.sweep_bits == "low" else S.config3_sweep()):
         by_zf.setdefault(zf, []).append(mode)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     print(f"{'mode':24s} {'zf':>4s} {'gemm ms':>9s} {'TOPS':>8s} {'trim GB/s':>10s}", file=sys.stderr)
@@ -199,7 +202,7 @@ def sweep(args, sq, S, torch, dev):
         "metric": "SPARQ conv-GEMM TOPS (int8-equiv)", "value": round(tops, 2), "unit": "TOPS", "n_gpus": 1,
         "steps": max(10, args.steps // 10), "warmup": max(5, args.warmup // 5), "ms_per_step": round(tot_ms / len(points), 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
-        "config": {"workload": f"config3 sweep: {len(points)} option points on GEMM M={args.rows} K=4608 N=512, "
+        "config": {"workload": f"config3 sweep ({'3-bit and 2-bit windows' if args.sweep_bits == 'low' else '4-bit windows'}): {len(points)} option points on GEMM M={args.rows} K=4608 N=512, "
                                f"{args.sweep_form} form (value = total ops / total time over the points)"},
         "points": points, "roofline": None, "cpu_baseline": None}), flush=True)
 

@@ -232,6 +232,18 @@ def config3_sweep():
     return pts
 
 
+def config3_sweep_low():
+    """24 (mode, zero fraction) points of the lower-budget variants (Section 5.1, Table 4): 3-bit windows with
+    6 shifts and 2-bit windows with 7 shifts, {floor, round} x pairing {off, on} x zero fraction {.2,.5,.8}."""
+    pts = []
+    for n, mask in ((3, OPT6_3B), (2, OPT7_2B)):
+        for rnd in (0, 1):
+            for pair in (0, 1):
+                for zf in (0.2, 0.5, 0.8):
+                    pts.append((Mode(n, mask, rnd, pair), zf))
+    return pts
+
+
 def config4(batch: int = 128, mode: Optional[Mode] = None) -> List[ConvLayer]:
     """Inception-v3-shaped mixed convolutions, 50 % zeros, incl. odd channel counts."""
     m = mode or Mode(4, OPT5, 1, 1)

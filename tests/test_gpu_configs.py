@@ -125,6 +125,17 @@ def test_config3_sweep_all_36_points_small_m(sq, oracle, mode, zf):
     check_sampled(sq, oracle, 3, replace(S.config3_layer(1024 + 77), mode=mode, zf=zf), n=48)
 
 
+@pytest.mark.parametrize("mode,zf", S.config3_sweep_low(), ids=lambda v: v.label if isinstance(v, S.Mode) else f"zf{v}")
+def test_config3_low_bit_sweep_all_24_points_small_m(sq, oracle, mode, zf):
+    """3-bit / 6-shift and 2-bit / 7-shift windows, with and without pairing (a zero partner grants 6 / 4 bits)."""
+    check_sampled(sq, oracle, 3, replace(S.config3_layer(1024 + 77), mode=mode, zf=zf), n=48)
+
+
+def test_config3_full_size_as_convolution_low_bit(sq, oracle):
+    layer = replace(S.config3_layer(), name="conv3x3_512_512_32x32", B=64, H=32, W=32, C=512, KH=3, KW=3, pad=(1, 1))
+    check_sampled(sq, oracle, 3, layer, n=2048, modes=[S.Mode(3, S.OPT6_3B, 1, 1), S.Mode(2, S.OPT7_2B, 0, 0)])
+
+
 # ---- config 4: Inception-v3-shaped layers, batch 128, 4-bit 5opt and 2-bit 7opt ---------------------
 @pytest.mark.parametrize("layer", S.config4(), ids=lambda l: l.name)
 def test_config4_inception_4bit_and_2bit(sq, oracle, layer):
