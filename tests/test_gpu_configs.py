@@ -142,3 +142,45 @@ def test_config4_inception_4bit_and_2bit(sq, oracle, layer):
     """Both passes of the workload on the same tensors: 4-bit 5opt rounding, then the 2-bit window
     with 7 shifts where a zero partner grants 4 bits."""
     check_sampled(sq, oracle, 4, layer, n=512, modes=[layer.mode, S.Mode(2, S.OPT7_2B, 1, 1)])
+
+
+# ---- sizes at the limits of the index arithmetic ------------------------------------------------------
+def _big_1x1(sq, oracle, pixels, C, N, seed):
+    """A 1x1 layer over `pixels` pixels whose activations repeat a seeded 32 MiB block (fast to generate)."""
+    layer = S.ConvLayer(f"big_{pixels}x{C}x{N}", 1, pixels, 1, C, N)
+    rng = S.rng_for(5, seed)
+    block = S.gen_activations((1 << 25,), 0.5, rng)
+    x = np.resize(block, layer.x_shape())
+    w = S.gen_weights(layer.w_shape(), rng)
+    sc = S.gen_scales(N, rng)
+    _check_one(sq, oracle, layer, (x, w, sc), 512)
+
+
+def test_patch_kernel_at_its_largest_row_count(sq, oracle):
+    """M = 2^22 - 5: the last M the reciprocal divisions of the input-patch kernel accept, with a ragged last tile."""
+    d = sq.conv_desc(1, (1 << 22) - 5, 1, 64, 64, 1, 1, (1, 1), (0, 0))
+    assert "conv_patch_kernel" in sq.sparq_conv_plan(d, sq.mode(4, S.OPT5, 1, 1))
+    _big_1x1(sq, oracle, (1 << 22) - 5, 64, 64, 1)
+
+
+def test_row_count_past_the_patch_kernel_limit_takes_the_gather_kernel(sq, oracle):
+    d = sq.conv_desc(1, (1 << 22) + 3, 1, 64, 64, 1, 1, (1, 1), (0, 0))
+    assert "conv_gemm_kernel" in sq.sparq_conv_plan(d, sq.mode(4, S.OPT5, 1, 1))
+    _big_1x1(sq, oracle, (1 << 22) + 3, 64, 64, 2)
+
+
+def test_input_just_below_two_gib(sq, oracle):
+    """x of 2^31 - 64 * 7 bytes (offsets are 32-bit with the top bit marking padding); outputs of 2 GiB each."""
+    _big_1x1(sq, oracle, (1 << 25) - 7, 64, 16, 3)
+
+
+def test_input_of_two_gib_is_refused(sq):
+    d = sq.conv_desc(1, 1 << 25, 1, 64, 16, 1, 1, (1, 1), (0, 0))
+    m = sq.mode(4, S.OPT5, 1, 1)
+    packed = torch.empty(sq.sparq_packed_bytes(d), dtype=torch.uint8, device="cuda:0")
+    x = torch.empty(1 << 31, dtype=torch.uint8, device="cuda:0")
+    out = torch.empty(((1 << 25), 16), dtype=torch.float32, device="cuda:0")
+    sc = torch.ones(16, dtype=torch.float32, device="cuda:0")
+    with pytest.raises(sq.SparqError):
+        sq.sparq_conv_gemm(x, packed, d, m, scale=sc, out=out)
+
