@@ -194,16 +194,26 @@ inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_
 
 inline sparq_status launch_status() { return hipGetLastError() == hipSuccess ? SPARQ_OK : SPARQ_ELAUNCH; }
 
-// Number of compute units of the current device (queried once).
+// Per-device bookkeeping (kernel attributes set, CU counts) is kept in small tables indexed by the HIP device
+// ordinal; ordinals past the table share its last slot, which only costs repeated attribute calls.
+constexpr int kMaxDevices = 16;
+inline int current_device_slot() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0) dev = 0;
+    return dev < kMaxDevices ? dev : kMaxDevices - 1;
+}
+
+// Number of compute units of the current device (queried once per device).
 inline int device_cu_count() {
-    static int cus = 0;
-    if (cus == 0) {
+    static int cus[kMaxDevices] = {};
+    const int slot = current_device_slot();
+    if (cus[slot] == 0) {
         int dev = 0;
         hipDeviceProp_t prop;
         if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 256;
-        cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+        cus[slot] = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     }
-    return cus;
+    return cus[slot];
 }
 
 // Implemented in sparq_elementwise.hip: trimmed copy of x with channels padded to Cp.

@@ -375,7 +375,10 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
 
 template <class Cfg, int KIND>
 sparq_status launch_cfg(const GemmParams& p, hipStream_t s) {
-    static bool attr_set = false;
+    static bool attr_set_dev[kMaxDevices] = {};      // per device
+    const int slot = current_device_slot();
+    bool& attr_set = attr_set_dev[slot];
+    if (slot == kMaxDevices - 1) attr_set = false;
     auto kern = conv_gemm_kernel<Cfg, KIND>;
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,

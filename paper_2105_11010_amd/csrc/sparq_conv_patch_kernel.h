@@ -551,8 +551,9 @@ sparq_status launch_patch_cfg(const PatchParams& p, int npix_max, hipStream_t s)
         ((q.nsteps - Cfg::kUnrolled) & 1))
         return SPARQ_EUNSUPPORTED;
     auto kern = conv_patch_kernel<Cfg, KIND>;
-    static int lds_set = 0;
-    if (lds_bytes > lds_set) {
+    static int lds_set_dev[kMaxDevices] = {};        // largest dynamic LDS size enabled so far, per device
+    int& lds_set = lds_set_dev[current_device_slot()];
+    if (lds_bytes > lds_set || current_device_slot() == kMaxDevices - 1) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 lds_bytes) != hipSuccess)
             return SPARQ_ELAUNCH;
