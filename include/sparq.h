@@ -137,12 +137,19 @@ sparq_status sparq_dequant(const int32_t *acc, const float *scale, float *out,
  * so that y is the NHWC uint8 input of the next layer and its lower clamp is
  * the ReLU.  The product and the rounding (to nearest, ties to even) are done
  * in fp32: y is defined by exactly that arithmetic.  Neither acc nor a float
- * tensor is written: one byte leaves per output instead of four.  factor and y
- * (both device memory) must be 16-byte aligned; everything else as for
- * sparq_conv_gemm with acc == NULL, including the workspace. */
+ * tensor is written: one byte leaves per output instead of four.
+ * out_mode (NULL or window_bits = 8: none) additionally trims y as the NEXT
+ * layer would on loading it, y = T(y) with pairs (2j, 2j+1) of one pixel's N
+ * channels (Sections 3.1-3.2), so that the next layer can run with
+ * window_bits = 8 and every activation is trimmed once.  This happens inside
+ * the convolution's epilogue when out_mode equals mode and N is a multiple of
+ * 4, and as one in-place sparq_trim pass over y otherwise; the result is the
+ * same.  factor and y (both device memory) must be 16-byte aligned;
+ * everything else as for sparq_conv_gemm with acc == NULL, including the
+ * workspace. */
 sparq_status sparq_conv_gemm_u8(const uint8_t *x, const void *packed_w,
                                 const sparq_conv_desc *desc, const sparq_mode *mode,
-                                const float *factor, uint8_t *y,
+                                const float *factor, uint8_t *y, const sparq_mode *out_mode,
                                 void *workspace, size_t workspace_bytes, void *stream);
 
 /* The requantisation of sparq_conv_gemm_u8 as a pass of its own over int32

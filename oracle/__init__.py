@@ -173,8 +173,11 @@ def requant(acc: np.ndarray, factor: np.ndarray) -> np.ndarray:
     return y
 
 
-def conv_gemm_u8(x: np.ndarray, w: np.ndarray, factor: np.ndarray, stride=(1, 1), pad=(0, 0), *, rows=None, **mode):
-    """The trimmed convolution followed by the requantisation of its int32 result: uint8 [M or len(rows), N]."""
+def conv_gemm_u8(x: np.ndarray, w: np.ndarray, factor: np.ndarray, stride=(1, 1), pad=(0, 0), *, rows=None,
+                 out_mode=None, **mode):
+    """The trimmed convolution followed by the requantisation of its int32 result: uint8 [M or len(rows), N].
+    out_mode (a dict of trim() keywords) trims the bytes as the next layer would: pairs along the N channels of a row."""
     acc, _ = conv_gemm(x, w, stride, pad, rows=rows, **mode)
-    return requant(acc, factor)
+    y = requant(acc, factor)
+    return trim(y, **out_mode) if out_mode else y
 

@@ -56,7 +56,7 @@ def _load() -> ctypes.CDLL:
     L.sparq_conv_gemm.restype = ctypes.c_int
     L.sparq_dequant.argtypes = [vp, vp, vp, i64, i32, vp]
     L.sparq_dequant.restype = ctypes.c_int
-    L.sparq_conv_gemm_u8.argtypes = [vp, vp, pd, pm, vp, vp, vp, sz, vp]
+    L.sparq_conv_gemm_u8.argtypes = [vp, vp, pd, pm, vp, vp, pm, vp, sz, vp]
     L.sparq_conv_gemm_u8.restype = ctypes.c_int
     L.sparq_requant.argtypes = [vp, vp, vp, i64, i32, vp]
     L.sparq_requant.restype = ctypes.c_int
@@ -163,8 +163,10 @@ def sparq_dequant(acc: torch.Tensor, scale: torch.Tensor, out: torch.Tensor) -> 
 
 
 def sparq_conv_gemm_u8(x: torch.Tensor, packed: torch.Tensor, d: SparqConvDesc, m: SparqMode, factor: torch.Tensor,
-                       y: torch.Tensor, workspace: Optional[torch.Tensor] = None) -> None:
-    """The convolution with its result requantised to uint8 (y holds M*N bytes: the next layer's NHWC input)."""
+                       y: torch.Tensor, workspace: Optional[torch.Tensor] = None,
+                       out_mode: Optional[SparqMode] = None) -> None:
+    """The convolution with its result requantised to uint8 (y holds M*N bytes: the next layer's NHWC input),
+    optionally trimmed with out_mode as the next layer would trim it on loading."""
     if x.numel() != d.B * d.H * d.W * d.C:
         raise ValueError("activation size does not match the descriptor")
     if y.numel() != out_rows(d) * d.N:
@@ -175,6 +177,7 @@ def sparq_conv_gemm_u8(x: torch.Tensor, packed: torch.Tensor, d: SparqConvDesc, 
     ws_bytes = workspace.numel() if workspace is not None else 0
     _check(lib.sparq_conv_gemm_u8(_dev(x, torch.uint8, "x"), _dev(packed, torch.uint8, "packed"), ctypes.byref(d),
                                   ctypes.byref(m), _dev(factor, torch.float32, "factor"), _dev(y, torch.uint8, "y"),
+                                  ctypes.byref(out_mode) if out_mode is not None else None,
                                   ws_ptr, ws_bytes, _stream()), "sparq_conv_gemm_u8")
 
 

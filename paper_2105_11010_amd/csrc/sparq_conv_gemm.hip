@@ -253,12 +253,20 @@ namespace {
 // Both convolution entry points: acc / out (with scale) as in sparq_conv_gemm, or y (with scale holding the
 // requantisation factors) as in sparq_conv_gemm_u8.
 sparq_status conv_launch(const uint8_t* x, const void* packed_w, const sparq_conv_desc* desc, const sparq_mode* mode,
-                         int32_t* acc, const float* scale, float* out, uint8_t* y, void* workspace,
-                         size_t workspace_bytes, void* stream) {
+                         int32_t* acc, const float* scale, float* out, uint8_t* y, const sparq_mode* out_mode,
+                         void* workspace, size_t workspace_bytes, void* stream) {
     ConvGeom g;
     if (!x || !packed_w || !conv_geom(desc, &g) || !mode_valid(mode)) return SPARQ_EINVAL;
     if (!acc && !out && !y) return SPARQ_EINVAL;
     if ((out || y) && !scale) return SPARQ_EINVAL;
+    // y trimmed for the next layer: in the epilogue when that layer's mode is this layer's own and the kernel
+    // packs the bytes (N a multiple of 4, no split reduction, not a plain 8-bit layer); otherwise one in-place
+    // pass of the standalone trim over y afterwards.  Either way y = trim(requantised result), pairs (2j, 2j+1) of a row.
+    const bool trim_y = y && out_mode && out_mode->window_bits != 8;
+    if (trim_y && !mode_valid(out_mode)) return SPARQ_EINVAL;
+    const bool same_mode = trim_y && out_mode->window_bits == mode->window_bits && out_mode->shift_mask == mode->shift_mask &&
+                           out_mode->round_nearest == mode->round_nearest && out_mode->pair == mode->pair;
+    bool fused_trim = same_mode && g.N % 4 == 0;
     if (!aligned(x, 16) || !aligned(packed_w, 256) || (acc && !aligned(acc, 16)) || (out && !aligned(out, 16)) ||
         (y && !aligned(y, 16)) || (scale && !aligned(scale, 16)))
         return SPARQ_EINVAL;
@@ -296,7 +304,9 @@ sparq_status conv_launch(const uint8_t* x, const void* packed_w, const sparq_con
         p.luts = make_luts(8, 1);
         ConvGeom ft = f;
         ft.Np = g.Np;
-        return pick_tile(ft, y != nullptr)(kTrimNone, p, s);
+        const sparq_status stf = pick_tile(ft, y != nullptr)(kTrimNone, p, s);
+        if (stf != SPARQ_OK || !trim_y) return stf;
+        return sparq_trim(y, y, g.M, g.N, out_mode, stream);
     }
     if (g.Cp != g.C) {
         // Channel counts that are not a multiple of 16: trim into a channel-padded copy
@@ -309,8 +319,13 @@ sparq_status conv_launch(const uint8_t* x, const void* packed_w, const sparq_con
         if (st != SPARQ_OK) return st;
         xin = static_cast<const uint8_t*>(workspace);
         kind = kTrimNone;
+        fused_trim = false;                     // the kernel runs with trimming off
     }
     if (x_bytes >= kInvalidOffset) return SPARQ_EUNSUPPORTED;
+    const auto finish = [&](sparq_status st, bool fused) {
+        if (st != SPARQ_OK || !trim_y || fused) return st;
+        return sparq_trim(y, y, g.M, g.N, out_mode, stream);
+    };
 
     // Preferred: the input-patch kernel (activations loaded and trimmed once per tile and channel
     // block).  SPARQ_PATH=gather|patch (a tuning knob, not part of the interface) forces one of the two kernels.
@@ -319,7 +334,7 @@ sparq_status conv_launch(const uint8_t* x, const void* packed_w, const sparq_con
         q.x = xin;
         q.wpk = static_cast<const uint8_t*>(packed_w) + g.w_off;
         q.colsum = static_cast<const int32_t*>(packed_w);
-        q.acc = acc; q.scale = scale; q.out = out; q.out_u8 = y;
+        q.acc = acc; q.scale = scale; q.out = out; q.out_u8 = y; q.trim_out = fused_trim ? 1 : 0;
         q.x_bytes = (uint32_t)x_bytes;
         q.w_bytes = (uint32_t)((size_t)g.Kp * g.Np);
         q.N = g.N; q.Np = g.Np; q.C = g.Cp;
@@ -338,11 +353,11 @@ sparq_status conv_launch(const uint8_t* x, const void* packed_w, const sparq_con
             st = pl.variant->fn_split(kind, q, pl.npix, s);
             if (st == SPARQ_OK && out) st = sparq_dequant(sum, scale, out, g.M, g.N, stream);
             if (st == SPARQ_OK && y) st = sparq_requant(sum, scale, y, g.M, g.N, stream);
-            if (st != SPARQ_EUNSUPPORTED) return st;
+            if (st != SPARQ_EUNSUPPORTED) return finish(st, false);
         } else {
             const PatchLauncher fn = pl.ws ? pl.variant->fn_ws : pl.variant->fn;
             const sparq_status st = fn(kind, q, pl.npix, s);
-            if (st != SPARQ_EUNSUPPORTED) return st;
+            if (st != SPARQ_EUNSUPPORTED) return finish(st, fused_trim);
         }
     }
 
@@ -354,6 +369,7 @@ sparq_status conv_launch(const uint8_t* x, const void* packed_w, const sparq_con
     p.scale = scale;
     p.out = out;
     p.out_u8 = y;
+    p.trim_out = fused_trim ? 1 : 0;
     p.M = g.M;
     p.x_bytes = (uint32_t)x_bytes;
     p.N = g.N; p.Np = g.Np; p.Kk = g.Kk; p.nkb = g.Kp / kStepK; p.scale_n = g.N;
@@ -363,7 +379,7 @@ sparq_status conv_launch(const uint8_t* x, const void* packed_w, const sparq_con
     p.rcp_kw = 1.0f / (float)g.KW;
     p.luts = make_luts(mode->window_bits, mode->shift_mask);
 
-    return pick_tile(g, y != nullptr)(kind, p, s);
+    return finish(pick_tile(g, y != nullptr)(kind, p, s), fused_trim);
 }
 
 }  // namespace
@@ -372,12 +388,13 @@ extern "C" sparq_status sparq_conv_gemm(const uint8_t* x, const void* packed_w, 
                                         const sparq_mode* mode, int32_t* acc, const float* scale, float* out,
                                         void* workspace, size_t workspace_bytes, void* stream) {
     if (!acc && !out) return SPARQ_EINVAL;
-    return conv_launch(x, packed_w, desc, mode, acc, scale, out, nullptr, workspace, workspace_bytes, stream);
+    return conv_launch(x, packed_w, desc, mode, acc, scale, out, nullptr, nullptr, workspace, workspace_bytes, stream);
 }
 
 extern "C" sparq_status sparq_conv_gemm_u8(const uint8_t* x, const void* packed_w, const sparq_conv_desc* desc,
                                            const sparq_mode* mode, const float* factor, uint8_t* y,
-                                           void* workspace, size_t workspace_bytes, void* stream) {
+                                           const sparq_mode* out_mode, void* workspace, size_t workspace_bytes,
+                                           void* stream) {
     if (!factor || !y) return SPARQ_EINVAL;
-    return conv_launch(x, packed_w, desc, mode, nullptr, factor, nullptr, y, workspace, workspace_bytes, stream);
+    return conv_launch(x, packed_w, desc, mode, nullptr, factor, nullptr, y, out_mode, workspace, workspace_bytes, stream);
 }

@@ -34,6 +34,7 @@ struct GemmParams {
     const float* scale;      // [N] or null
     float* out;              // [M][N] or null
     uint8_t* out_u8;         // [M][N] requantised output or null (then it is the only output; scale holds its factors)
+    int trim_out;            // out_u8 with N % 4 == 0 only: trim the requantised bytes with this launch's own mode as well
     int64_t M;
     uint32_t x_bytes;
     int N, Np, Kk, nkb;
@@ -336,7 +337,8 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
             // Requantised bytes, N a multiple of 4: the four rows a lane holds of one channel are exchanged
             // inside groups of four lanes for four channels of one row: one 32-bit store instead of four byte
             // stores (the byte form is bound by the number of store instructions).
-            auto store_tile_u8_packed = [&]() __attribute__((always_inline)) {
+            auto store_tile_u8_packed = [&](auto trim_) __attribute__((always_inline)) {
+                constexpr bool kTrimOut = decltype(trim_)::value;   // the next layer's trim applied here, once per result
                 const int pitch = p.N;
                 const __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc(
                     (void*)(p.out_u8 + m0 * p.N), 0, rows * pitch, 0x00020000);
@@ -356,15 +358,19 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
                         for (int q = 0; q < 4; ++q) {
                             const uint32_t w = requant_u8x4(c[i][j][4 * q] + corr, c[i][j][4 * q + 1] + corr, c[i][j][4 * q + 2] + corr,
                                                             c[i][j][4 * q + 3] + corr, sc);
-                            __builtin_amdgcn_raw_buffer_store_b32((int)quad_transpose_bytes(w, qs), orsrc,
-                                                                  (int)(lane_off + (uint32_t)((i * 32 + 8 * q) * pitch)), 0, 0);
+                            // after the transpose the word holds channels n4 .. n4+3 of one pixel: two pairs
+                            uint32_t t = quad_transpose_bytes(w, qs);
+                            if constexpr (kTrimOut) t = trim4_kind<KIND>(t, p.luts);
+                            __builtin_amdgcn_raw_buffer_store_b32((int)t, orsrc, (int)(lane_off + (uint32_t)((i * 32 + 8 * q) * pitch)), 0, 0);
                         }
                 }
             };
             if (Cfg::kByteOutput && p.out_u8) {
                 if constexpr (Cfg::kByteOutput) {
-                    if ((p.N & 3) == 0) store_tile_u8_packed();
-                    else store_tile(std::false_type{}, std::false_type{}, std::true_type{});
+                    if ((p.N & 3) == 0) {
+                        if (KIND != kTrimNone && p.trim_out) store_tile_u8_packed(std::true_type{});
+                        else store_tile_u8_packed(std::false_type{});
+                    } else store_tile(std::false_type{}, std::false_type{}, std::true_type{});
                 }
             } else if (p.acc && p.out) store_tile(std::true_type{}, std::true_type{}, std::false_type{});
             else if (p.out) store_tile(std::false_type{}, std::true_type{}, std::false_type{});

@@ -42,6 +42,7 @@ struct PatchParams {
     const float* scale;      // [N] or null
     float* out;              // [M][N] or null
     uint8_t* out_u8;         // [M][N] requantised output or null (then it is the only output; scale holds its factors)
+    int trim_out;            // out_u8 with N % 4 == 0 only: trim the requantised bytes with this launch's own mode as well
     uint32_t x_bytes, w_bytes;
     int N, Np, C;
     int ncb;                 // channel blocks (units) per work item
@@ -480,7 +481,8 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
                 // Requantised bytes, N a multiple of 4: the four rows a lane holds of one channel are exchanged
                 // inside groups of four lanes for four channels of one row: one 32-bit store instead of four
                 // byte stores (the byte form is bound by the number of store instructions).
-                auto store_tile_u8_packed = [&]() __attribute__((always_inline)) {
+                auto store_tile_u8_packed = [&](auto trim_) __attribute__((always_inline)) {
+                    constexpr bool kTrimOut = decltype(trim_)::value;   // the next layer's trim applied here, once per result
                     const int pitch = p.N;
                     const __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc(
                         (void*)(p.out_u8 + m0 * p.N), 0, rows * pitch, 0x00020000);
@@ -500,12 +502,17 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
                             for (int j = 0; j < FN; ++j) {
                                 const uint32_t w = requant_u8x4(c[i][j][4 * q] + corr[j], c[i][j][4 * q + 1] + corr[j], c[i][j][4 * q + 2] + corr[j],
                                                             c[i][j][4 * q + 3] + corr[j], sc[j]);
-                                __builtin_amdgcn_raw_buffer_store_b32((int)quad_transpose_bytes(w, qs), orsrc,
-                                                                      (int)(lane_off[j] + (uint32_t)row_bytes), 0, 0);
+                                // after the transpose the word holds channels n4 .. n4+3 of one pixel: two pairs
+                                uint32_t t = quad_transpose_bytes(w, qs);
+                                if constexpr (kTrimOut) t = trim4_kind<KIND>(t, p.luts);
+                                __builtin_amdgcn_raw_buffer_store_b32((int)t, orsrc, (int)(lane_off[j] + (uint32_t)row_bytes), 0, 0);
                             }
                         }
                 };
-                if (p.out_u8 && (p.N & 3) == 0) store_tile_u8_packed();
+                if (p.out_u8 && (p.N & 3) == 0) {
+                    if (KIND != kTrimNone && p.trim_out) store_tile_u8_packed(std::true_type{});
+                    else store_tile_u8_packed(std::false_type{});
+                }
                 else if (p.out_u8) store_tile(std::false_type{}, std::false_type{}, std::true_type{});
                 else if (p.acc && p.out) store_tile(std::true_type{}, std::true_type{}, std::false_type{});
                 else if (p.out) store_tile(std::false_type{}, std::true_type{}, std::false_type{});

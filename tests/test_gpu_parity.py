@@ -123,7 +123,7 @@ def test_requant(sq, oracle, M, N):
     assert np.array_equal(y.cpu().numpy(), oracle.requant(acc, f))
 
 
-def run_conv_u8(sq, x, w, f, layer, mode):
+def run_conv_u8(sq, x, w, f, layer, mode, out_mode=None):
     d = sq.conv_desc(layer.B, layer.H, layer.W, layer.C, layer.N, layer.KH, layer.KW, layer.stride, layer.pad)
     m = sq.mode(*mode.astuple())
     packed = torch.empty(sq.sparq_packed_bytes(d), dtype=torch.uint8, device="cuda:0")
@@ -131,17 +131,20 @@ def run_conv_u8(sq, x, w, f, layer, mode):
     wsb = sq.sparq_workspace_bytes(d, m)
     ws = torch.empty(wsb, dtype=torch.uint8, device="cuda:0") if wsb else None
     y = torch.full((layer.M, layer.N), 7, dtype=torch.uint8, device="cuda:0")
-    sq.sparq_conv_gemm_u8(dev(x), packed, d, m, dev(f), y, workspace=ws)
+    sq.sparq_conv_gemm_u8(dev(x), packed, d, m, dev(f), y, workspace=ws,
+                          out_mode=sq.mode(*out_mode.astuple()) if out_mode else None)
     torch.cuda.synchronize()
     return y.cpu().numpy()
 
 
-def check_layer_u8(sq, oracle, layer, mode, seed_cfg=8):
-    """Requantised uint8 output of the fused convolution: every byte equals the oracle's."""
+def check_layer_u8(sq, oracle, layer, mode, seed_cfg=8, out_mode=None):
+    """Requantised uint8 output of the fused convolution (optionally trimmed for the next layer): every byte
+    equals the oracle's."""
     x, w, _ = S.gen_layer(seed_cfg, layer)
     f = S.gen_requant(layer, S.rng_for(seed_cfg, 900 + layer.index))
-    y = run_conv_u8(sq, x, w, f, layer, mode)
-    ref = oracle.conv_gemm_u8(x, w, f, layer.stride, layer.pad, **mode.kwargs())
+    y = run_conv_u8(sq, x, w, f, layer, mode, out_mode)
+    ref = oracle.conv_gemm_u8(x, w, f, layer.stride, layer.pad, out_mode=out_mode.kwargs() if out_mode else None,
+                              **mode.kwargs())
     assert np.array_equal(y, ref), f"{layer.name} {mode.label}: uint8 mismatch"
     assert (ref == 0).any() and ref.max() > 60, "degenerate test case"
 
@@ -255,6 +258,37 @@ def test_conv_patch_shapes(sq, oracle, layer, mode, path):
 def test_conv_u8_shapes(sq, oracle, layer, path):
     """The requantised-output entry point on every shape and through every kernel form."""
     check_layer_u8(sq, oracle, layer, S.Mode(4, S.OPT5, 1, 1), seed_cfg=9)
+
+
+@pytest.mark.parametrize("layer", SHAPES + PATCH_SHAPES, ids=lambda l: l.name)
+@pytest.mark.parametrize("mode", [S.Mode(4, S.OPT5, 1, 1), S.Mode(3, S.OPT6_3B, 0, 1)], ids=lambda m: m.label)
+def test_conv_u8_trimmed_for_the_next_layer(sq, oracle, layer, mode, path):
+    """Output trimmed with the layer's own mode: inside the epilogue where N is a multiple of 4, by a pass of the
+    standalone trim otherwise (odd N: the last channel of a pixel has no partner)."""
+    check_layer_u8(sq, oracle, layer, mode, seed_cfg=9, out_mode=mode)
+
+
+@pytest.mark.parametrize("mode,out_mode", [(S.PLAIN8, S.Mode(4, S.OPT5, 1, 1)), (S.Mode(4, S.OPT5, 1, 1), S.Mode(4, S.OPT3, 0, 0)),
+                                           (S.Mode(4, S.OPT2, 0, 1), S.PLAIN8)], ids=["plain-to-5opt", "5opt-to-3opt", "2opt-to-plain"])
+def test_conv_u8_trimmed_with_another_mode(sq, oracle, mode, out_mode):
+    """A first layer at plain 8 bits feeding a trimmed one, two different modes, and no output trim."""
+    for layer in (S.ConvLayer("u8_tm_a", 2, 12, 12, 64, 96, 3, 3, (1, 1), (1, 1)), S.ConvLayer("u8_tm_b", 1, 9, 30, 3, 64, 7, 7, (2, 2), (3, 3))):
+        check_layer_u8(sq, oracle, layer, mode, seed_cfg=9, out_mode=out_mode)
+
+
+def test_conv_u8_trimmed_chain_runs_the_second_layer_untrimmed(sq, oracle):
+    """Layer 1 trims its output for layer 2; layer 2 at plain 8 bits then equals layer 2 trimming on load."""
+    l1 = S.ConvLayer("tchain1", 2, 12, 12, 64, 96, 3, 3, (1, 1), (1, 1))
+    l2 = S.ConvLayer("tchain2", 2, 12, 12, 96, 40, 1, 1, index=1)
+    mode = S.Mode(4, S.OPT5, 1, 1)
+    x, w1, _ = S.gen_layer(9, l1)
+    _, w2, _ = S.gen_layer(9, l2)
+    f1, f2 = S.gen_requant(l1, S.rng_for(9, 950)), S.gen_requant(l2, S.rng_for(9, 951))
+    y1t = run_conv_u8(sq, x, w1, f1, l1, mode, out_mode=mode)
+    y2 = run_conv_u8(sq, y1t.reshape(l2.x_shape()), w2, f2, l2, S.PLAIN8)
+    r1 = oracle.conv_gemm_u8(x, w1, f1, l1.stride, l1.pad, **mode.kwargs())            # untrimmed bytes
+    r2 = oracle.conv_gemm_u8(r1.reshape(l2.x_shape()), w2, f2, l2.stride, l2.pad, **mode.kwargs())   # trimmed on load
+    assert np.array_equal(y1t, oracle.trim(r1, **mode.kwargs())) and np.array_equal(y2, r2)
 
 
 @pytest.mark.parametrize("tile", ["128x128", "128x256", "128x512"])
