@@ -52,9 +52,11 @@ def parse_args():
     ap.add_argument("--zf", type=float, default=None, help="cfg3 only: zero fraction override")
     ap.add_argument("--rows", type=int, default=65536, help="cfg3 only: M")
     ap.add_argument("--batch", type=int, default=None, help="cfg1/2/4: batch override")
-    ap.add_argument("--output", default="fp32", choices=["fp32", "u8"],
+    ap.add_argument("--output", default="fp32", choices=["fp32", "u8", "u8-chain"],
                     help="fp32: fused per-channel dequantisation (the headline form); u8: results requantised to the next "
-                         "layer's unsigned 8-bit activations (sparq_conv_gemm_u8)")
+                         "layer's unsigned 8-bit activations (sparq_conv_gemm_u8); u8-chain: the steady state of a chained "
+                         "network -- inputs arrive trimmed (the layer runs at plain 8 bits), outputs leave requantised and "
+                         "trimmed for the next layer, so every activation is trimmed once")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-layer", action="store_true", help="print a per-layer table on stderr")
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary figures of the default run")
@@ -120,18 +122,32 @@ def prepare(sq, S, torch, dev, cfg_id, layers, keep_host=False, outputs=("fp32",
         ws = torch.empty(wsb, dtype=torch.uint8, device=dev) if wsb else None
         out = torch.empty((layer.M, layer.N), dtype=torch.float32, device=dev) if "fp32" in outputs else None
         y = rq = None
-        if "u8" in outputs:
+        xt = m_out = None
+        if "u8" in outputs or "u8-chain" in outputs:
             y = torch.empty((layer.M, layer.N), dtype=torch.uint8, device=dev)
             rq = torch.from_numpy(S.gen_requant(layer, S.rng_for(cfg_id, 900 + layer.index))).to(dev)
-        items.append(dict(layer=layer, d=d, m=m, x=xd, sc=sd, packed=packed, ws=ws, out=out, y=y, rq=rq,
-                          host=(x, w, sc) if keep_host else None))
+        if "u8-chain" in outputs:
+            # what the previous layer would have handed over: x already trimmed with this layer's mode; the output is
+            # trimmed with the network's mode (a plain 8-bit first layer trims for the layers that follow it)
+            net_mode = next((l.mode for l in layers if l.mode.window_bits != 8), layer.mode)
+            xt = torch.empty_like(xd)
+            sq.sparq_trim(xd, xt, m)
+            m_out = sq.mode(*net_mode.astuple())
+            wsb2 = sq.sparq_workspace_bytes(d, sq.mode(*S.PLAIN8.astuple()))
+            if wsb2 > wsb:
+                ws = torch.empty(wsb2, dtype=torch.uint8, device=dev)
+        items.append(dict(layer=layer, d=d, m=m, x=xd, sc=sd, packed=packed, ws=ws, out=out, y=y, rq=rq, xt=xt, m_out=m_out,
+                          m_plain=sq.mode(*S.PLAIN8.astuple()), host=(x, w, sc) if keep_host else None))
         del wd
     torch.cuda.synchronize()
     return items
 
 
 def run_layer(sq, it, output="fp32"):
-    if output == "u8":
+    if output == "u8-chain":
+        sq.sparq_conv_gemm_u8(it["xt"], it["packed"], it["d"], it["m_plain"], it["rq"], it["y"], workspace=it["ws"],
+                              out_mode=it["m_out"])
+    elif output == "u8":
         sq.sparq_conv_gemm_u8(it["x"], it["packed"], it["d"], it["m"], it["rq"], it["y"], workspace=it["ws"])
     else:
         sq.sparq_conv_gemm(it["x"], it["packed"], it["d"], it["m"], acc=None, scale=it["sc"], out=it["out"],
@@ -257,7 +273,7 @@ def main():
                 "frac": round(dom_tops / PEAK_INT8_TOPS, 4),
                 "traffic": (tr["fetch_bytes"] + tr["write_bytes"]) if tr else None,
                 "traffic_detail": tr,
-                "algorithmic_bytes": x_b + w_b + (1 if args.output == "u8" else 4) * dom["layer"].M * dom["layer"].N,
+                "algorithmic_bytes": x_b + w_b + (4 if args.output == "fp32" else 1) * dom["layer"].M * dom["layer"].N,
                 "kernel": sq.sparq_conv_plan(dom["d"], dom["m"]), "layer": dom["layer"].name, "ms_per_launch": round(dom_ms, 4),
                 "ops_per_launch": dom["layer"].ops}
 
@@ -313,7 +329,7 @@ def main():
         for wl in ("cfg3", "cfg1", "cfg4"):
             a2 = argparse.Namespace(**{**vars(args), "workload": wl})
             c2, l2, n2 = build_workload(a2)
-            it2 = prepare(sq, S, torch, dev, c2, l2, outputs=("fp32", "u8"))
+            it2 = prepare(sq, S, torch, dev, c2, l2, outputs=("fp32", "u8", "u8-chain") if wl != "cfg3" else ("fp32",))
             ms2, _ = time_steps(sq, torch, it2, args.warmup, args.steps)
             also.append({"workload": n2, "value": round(S.total_ops(l2) / ms2 / 1e9, 2), "unit": "TOPS",
                          "ms_per_step": round(ms2, 4), "total_gop": round(S.total_ops(l2) / 1e9, 3)})
@@ -322,6 +338,11 @@ def main():
                 ms3, _ = time_steps(sq, torch, it2, args.warmup, args.steps, "u8")
                 also.append({"workload": n2 + ", uint8 requantised outputs", "value": round(S.total_ops(l2) / ms3 / 1e9, 2),
                              "unit": "TOPS", "ms_per_step": round(ms3, 4), "total_gop": round(S.total_ops(l2) / 1e9, 3)})
+                # and as the layers of a chained network: trimmed once, in the producer's epilogue
+                ms4, _ = time_steps(sq, torch, it2, args.warmup, args.steps, "u8-chain")
+                also.append({"workload": n2 + ", chained (input arrives trimmed; uint8 output trimmed for the next layer)",
+                             "value": round(S.total_ops(l2) / ms4 / 1e9, 2), "unit": "TOPS", "ms_per_step": round(ms4, 4),
+                             "total_gop": round(S.total_ops(l2) / 1e9, 3)})
             del it2
             torch.cuda.empty_cache()
 
@@ -368,7 +389,8 @@ def main():
         "dtype": "int8",
         "data": "synthetic",
         "config": {"workload": wl_name, "layers": sum(l.repeat for l in layers), "total_gop": round(total_ops / 1e9, 3),
-                   "output": "fp32 (fused dequant)" if args.output == "fp32" else "uint8 (fused requantisation)",
+                   "output": {"fp32": "fp32 (fused dequant)", "u8": "uint8 (fused requantisation)",
+                              "u8-chain": "uint8 (fused requantisation + the next layer's trim; input arrives trimmed)"}[args.output],
                    "wall_ms_per_step": round(wall_ms, 4)},
         "pct_int8_mfma_peak": round(100 * tops / PEAK_INT8_TOPS, 2),
         "roofline": roofline,

@@ -344,6 +344,23 @@ sparq_status conv_launch(const uint8_t* x, const void* packed_w, const sparq_con
         q.nsteps = g.KH * g.KW * pl.cbs;
         q.g = pl.pg;
         q.luts = make_luts(mode->window_bits, mode->shift_mask);
+        q.trim_in = 1;
+        TrimKind pkind = kind;
+        bool pfused = fused_trim;
+        // An input that arrives trimmed (mode: plain 8 bits) with an output to be trimmed for the next layer:
+        // the wave-specialised kernel of the OUTPUT mode, told not to trim its input, trims y in its epilogue.
+        // (A layer that would take the plain form takes the wave-specialised one here: that costs a few per cent,
+        // the separate trim pass over y it avoids costs more.)
+        bool use_ws = pl.ws;
+        if (trim_y && !fused_trim && !split && kind == kTrimNone && mode->window_bits == 8 && g.N % 4 == 0 &&
+            g.Cp == g.C && pl.variant->fn_ws) {
+            use_ws = true;
+            pkind = trim_kind(out_mode);
+            q.luts = make_luts(out_mode->window_bits, out_mode->shift_mask);
+            q.trim_in = 0;
+            pfused = true;
+        }
+        q.trim_out = pfused ? 1 : 0;
         if (split) {
             // partial sums are added into a cleared int32 buffer; the fp32 output is a second pass over it
             int32_t* sum = acc ? acc : reinterpret_cast<int32_t*>(static_cast<uint8_t*>(workspace) + pl.pad_bytes);
@@ -355,9 +372,9 @@ sparq_status conv_launch(const uint8_t* x, const void* packed_w, const sparq_con
             if (st == SPARQ_OK && y) st = sparq_requant(sum, scale, y, g.M, g.N, stream);
             if (st != SPARQ_EUNSUPPORTED) return finish(st, false);
         } else {
-            const PatchLauncher fn = pl.ws ? pl.variant->fn_ws : pl.variant->fn;
-            const sparq_status st = fn(kind, q, pl.npix, s);
-            if (st != SPARQ_EUNSUPPORTED) return finish(st, fused_trim);
+            const PatchLauncher fn = use_ws ? pl.variant->fn_ws : pl.variant->fn;
+            const sparq_status st = fn(pkind, q, pl.npix, s);
+            if (st != SPARQ_EUNSUPPORTED) return finish(st, pfused);
         }
     }
 

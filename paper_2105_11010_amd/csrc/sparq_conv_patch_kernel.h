@@ -43,6 +43,7 @@ struct PatchParams {
     float* out;              // [M][N] or null
     uint8_t* out_u8;         // [M][N] requantised output or null (then it is the only output; scale holds its factors)
     int trim_out;            // out_u8 with N % 4 == 0 only: trim the requantised bytes with this launch's own mode as well
+    int trim_in;             // 0: x is taken as it is (wave-specialised form only; elsewhere the instantiation decides)
     uint32_t x_bytes, w_bytes;
     int N, Np, C;
     int ncb;                 // channel blocks (units) per work item
@@ -162,8 +163,15 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
     // trim + flip to signed + write into the patch buffer at `buf`
     auto stage_chunk = [&](int i, uint8_t* buf) __attribute__((always_inline)) {
         v4u v = a_reg[i];
+        // The staging wavefronts' own loop can afford a (uniform) branch: a layer whose input was trimmed by its
+        // producer skips the trim here while the epilogue still trims the output with the same tables.
+        if (WS && KIND != kTrimNone && !p.trim_in) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = trim4_kind<KIND>(v[j], p.luts) ^ 0x80808080u;
+            for (int j = 0; j < 4; ++j) v[j] ^= 0x80808080u;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = trim4_kind<KIND>(v[j], p.luts) ^ 0x80808080u;
+        }
         const int pix = my_pix + i * (NT / PL);
         uint8_t* dst = (pix < stage_npix) ? buf + my_loff + i * (NT / PL) * kChunk : lds + dummy_off;
         *reinterpret_cast<v4u*>(dst) = v;
@@ -553,6 +561,7 @@ sparq_status launch_patch_cfg(const PatchParams& p, int npix_max, hipStream_t s)
     const int lds_bytes = 2 * Cfg::kPlanes * q.plane_stride + kChunk;     // two patch buffers + the dummy chunk
     if ((p.split_log2 != 0) != Cfg::kSplitK) return SPARQ_EUNSUPPORTED;
     if (p.g.rm_wo && !Cfg::kWaveSpecialised) return SPARQ_EUNSUPPORTED;
+    if (!p.trim_in && !Cfg::kWaveSpecialised && KIND != kTrimNone) return SPARQ_EUNSUPPORTED;
     if ((int64_t)p.N * 4 * kPatchTM >= 0x7FFFFFFF) return SPARQ_EUNSUPPORTED;   // 32-bit offsets inside a tile of results
     if (npix_max > Cfg::kMaxPix || lds_bytes > kLdsPerCu || q.nsteps < Cfg::kUnrolled ||
         ((q.nsteps - Cfg::kUnrolled) & 1))

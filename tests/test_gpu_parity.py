@@ -268,6 +268,13 @@ def test_conv_u8_trimmed_for_the_next_layer(sq, oracle, layer, mode, path):
     check_layer_u8(sq, oracle, layer, mode, seed_cfg=9, out_mode=mode)
 
 
+@pytest.mark.parametrize("layer", SHAPES + PATCH_SHAPES, ids=lambda l: l.name)
+def test_conv_u8_untrimmed_input_trimmed_output(sq, oracle, layer, path):
+    """The steady state of a chain: the input arrives trimmed (this layer runs at plain 8 bits) and the output is
+    trimmed for the next one -- in the wave-specialised kernels' epilogue, by a trim pass in the other forms."""
+    check_layer_u8(sq, oracle, layer, S.PLAIN8, seed_cfg=9, out_mode=S.Mode(4, S.OPT5, 1, 1))
+
+
 @pytest.mark.parametrize("mode,out_mode", [(S.PLAIN8, S.Mode(4, S.OPT5, 1, 1)), (S.Mode(4, S.OPT5, 1, 1), S.Mode(4, S.OPT3, 0, 0)),
                                            (S.Mode(4, S.OPT2, 0, 1), S.PLAIN8)], ids=["plain-to-5opt", "5opt-to-3opt", "2opt-to-plain"])
 def test_conv_u8_trimmed_with_another_mode(sq, oracle, mode, out_mode):
