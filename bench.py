@@ -32,8 +32,8 @@ PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E, published
 # chip (calibrated on the trim kernel, which reads and writes exactly the tensor's size), WRITE_SIZE
 # reads true KiB; the figures below are already scaled.
 MEASURED_TRAFFIC = {
-    "cfg3-conv": {"fetch_bytes": 128_430_000, "write_bytes": 134_220_000},
-    "cfg3": {"fetch_bytes": 346_990_000, "write_bytes": 139_200_000},
+    "cfg3-conv": {"fetch_bytes": 128_260_000, "write_bytes": 134_220_000},
+    "cfg3": {"fetch_bytes": 346_910_000, "write_bytes": 139_200_000},
 }
 
 
