@@ -111,3 +111,13 @@ def test_argument_validation_returns_codes(lib):
                                ctypes.c_size_t(0), None) == EINVAL                                     # workspace missing
     assert lib.sparq_conv_gemm(fake, fake, ctypes.byref(d_odd), ctypes.byref(m), fake, None, None, fake,
                                ctypes.c_size_t(16), None) == 3                                         # workspace too small
+    # the requantised-output entry point: factor and y are both required, y aligned, out_mode valid if given
+    u8 = (fake, fake, ctypes.byref(d), ctypes.byref(m))
+    assert lib.sparq_conv_gemm_u8(*u8, None, fake, None, None, ctypes.c_size_t(0), None) == EINVAL      # no factor
+    assert lib.sparq_conv_gemm_u8(*u8, fake, None, None, None, ctypes.c_size_t(0), None) == EINVAL      # no y
+    assert lib.sparq_conv_gemm_u8(*u8, fake, ctypes.c_void_p(0x1004), None, None, ctypes.c_size_t(0), None) == EINVAL
+    bad = Mode(4, 0x0F, 0, 1)
+    assert lib.sparq_conv_gemm_u8(*u8, fake, fake, ctypes.byref(bad), None, ctypes.c_size_t(0), None) == EINVAL
+    assert lib.sparq_conv_gemm_u8(fake, fake, ctypes.byref(d_odd), ctypes.byref(m), fake, fake, None, None,
+                                  ctypes.c_size_t(0), None) == EINVAL                                  # workspace missing
+
