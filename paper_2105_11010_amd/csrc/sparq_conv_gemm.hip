@@ -120,7 +120,7 @@ bool plan_patch(const ConvGeom& g, PatchGeom* pg, int* npix, int* ac, int* cbs) 
 
 // Output-channel tile and form of the patch kernel (rules fitted to per-layer measurements of the workload tables).
 //   64 for narrow layers (wave-specialised, two workgroups of 8 wavefronts per CU: the accumulators are small
-//   enough for 128 registers per lane).
+//   enough for 128 registers per lane), and for layers so small that 128-wide tiles would leave half the chip idle.
 //   256 (wave-specialised: 4 matrix + 4 staging wavefronts, one workgroup per CU) when it pads N to no more columns
 //   than 128-wide tiles would and either fills three quarters of the chip or the layer is small anyway (then one
 //   larger tile per CU beats a split reduction with its two extra launches); also for patches so large that LDS
@@ -135,6 +135,7 @@ const PatchVariant* pick_patch(const ConvGeom& g, int ac, int cbs, int npix, boo
     int tn = g.N <= 64 ? 64 : 128;
     const bool same_columns = round_up(g.N, 256) == round_up(g.N, 128);
     if (g.N > 128 && same_columns && (t256 * 4 >= (int64_t)cus * 3 || (t128 <= cus && t256 * 8 >= cus))) tn = 256;
+    if (g.N > 64 && t128 * 2 <= cus) tn = 64;      // a small layer: more, narrower tiles fill more CUs, and need no split reduction
     if (2 * 4 * cbs * patch_plane_stride(npix, 4 * cbs) > kLdsPerCu / 2) {
         if (g.N >= 256 && t256 >= cus) tn = 256;
         else if (g.N < 256 && t128 >= cus && !forced) return nullptr;   // narrow: gather kernel
