@@ -35,14 +35,45 @@ def sample_rows(layer, n=160, seed=0):
     return np.array(sorted(r for r in rows if 0 <= r < M), dtype=np.int64)
 
 
-def check_sampled(sq, oracle, cfg_id, layer, n=160, modes=None):
-    """Run `layer` at full size under each mode (default: the layer's own) on one set of tensors."""
+def check_sampled(sq, oracle, cfg_id, layer, n=160, modes=None, full=False):
+    """Run `layer` at full size under each mode (default: the layer's own) on one set of tensors.
+    full: the oracle recomputes EVERY output row, not a sample."""
     data = S.gen_layer(cfg_id, layer)
     for mode in modes or [layer.mode]:
-        _check_one(sq, oracle, replace(layer, mode=mode), data, n)
+        _check_one(sq, oracle, replace(layer, mode=mode), data, n, full)
 
 
-def _check_one(sq, oracle, layer, data, n):
+_PLANS = {}
+
+
+def bench_plans(sq, workload):
+    if workload not in _PLANS:
+        _PLANS[workload] = _bench_plans(sq, workload)
+    return _PLANS[workload]
+
+
+def _bench_plans(sq, workload):
+    """{layer name: plan line} of what `bench.py --workload <workload>` launches (its own layer list, batch and modes)."""
+    import argparse
+
+    import bench
+    args = argparse.Namespace(workload=workload, rows=65536, batch=None, mask=None, round=None, pair=None, zf=None)
+    _, layers, _ = bench.build_workload(args)
+    plans = {}
+    for l in layers:
+        d = sq.conv_desc(l.B, l.H, l.W, l.C, l.N, l.KH, l.KW, l.stride, l.pad)
+        plans[l.name] = sq.sparq_conv_plan(d, sq.mode(*l.mode.astuple()))
+    return plans
+
+
+def assert_plan_is_the_benchmarks(sq, workload, layer):
+    """The kernel and tiling this test runs for `layer` are the ones the benchmark times for it."""
+    d = sq.conv_desc(layer.B, layer.H, layer.W, layer.C, layer.N, layer.KH, layer.KW, layer.stride, layer.pad)
+    mine = sq.sparq_conv_plan(d, sq.mode(*layer.mode.astuple()))
+    assert mine == bench_plans(sq, workload)[layer.name], f"{layer.name}: tested {mine!r}, benchmark launches another plan"
+
+
+def _check_one(sq, oracle, layer, data, n, full=False):
     x, w, sc = data
     d = sq.conv_desc(layer.B, layer.H, layer.W, layer.C, layer.N, layer.KH, layer.KW, layer.stride, layer.pad)
     m = sq.mode(*layer.mode.astuple())
@@ -55,8 +86,8 @@ def _check_one(sq, oracle, layer, data, n):
     acc = torch.empty((layer.M, layer.N), dtype=torch.int32, device=dev)
     out = torch.empty((layer.M, layer.N), dtype=torch.float32, device=dev)
     sq.sparq_conv_gemm(xd, packed, d, m, acc=acc, scale=sd, out=out, workspace=ws)
-    rows = sample_rows(layer, n, seed=layer.index)
-    ridx = torch.from_numpy(rows).to(dev)
+    rows = None if full else sample_rows(layer, n, seed=layer.index)
+    ridx = torch.from_numpy(rows).to(dev) if rows is not None else slice(None)
     got_acc = acc[ridx].cpu().numpy()
     got_out = out[ridx].cpu().numpy()
     # a property that holds at any size: the fused fp32 output is the dequantised accumulator
@@ -83,41 +114,51 @@ def _check_one(sq, oracle, layer, data, n):
     assert np.array_equal(got_y, oracle.requant(ref_acc, fq)), f"{layer.name} {layer.mode.label}: uint8 mismatch on sampled rows"
 
 
-# ---- config 1: ResNet-18, batch 32, 3opt floor (first conv plain 8-bit) --------------------------
+# ---- config 0: the single 3x3 convolution, every output compared ----------------------------------
+def test_config0_every_output(sq, oracle):
+    layer = S.config0()[0]
+    assert_plan_is_the_benchmarks(sq, "cfg0", layer)
+    check_sampled(sq, oracle, 0, layer, full=True)
+
+
+# ---- config 1: ResNet-18, batch 32, 3opt floor (first conv plain 8-bit): every output compared ----
 @pytest.mark.parametrize("layer", S.config1(), ids=lambda l: l.name)
-def test_config1_resnet18(sq, oracle, layer):
-    check_sampled(sq, oracle, 1, layer, n=1024)
+def test_config1_resnet18_every_output(sq, oracle, layer):
+    assert_plan_is_the_benchmarks(sq, "cfg1", layer)
+    check_sampled(sq, oracle, 1, layer, full=True)
 
 
-# ---- config 2: ResNet-50, batch 256, 5opt round ---------------------------------------------------
-_C2 = S.config2()
-_C2_FULL = {"conv1_7x7s2", "s1b1_1x1_64_256", "s1bx_1x1_256_64", "s2b1_3x3s2_128", "s2proj_1x1s2_256_512",
-            "s3bx_3x3_256", "s4bx_3x3_512", "s4bx_1x1_512_2048"}
-
-
-@pytest.mark.parametrize("layer", [l for l in _C2 if l.name in _C2_FULL], ids=lambda l: l.name)
-def test_config2_resnet50_full_batch(sq, oracle, layer):
-    """The largest tensors of the stack at batch 256 (input up to 205 MB, fp32 output up to 822 MB)."""
+# ---- config 2: ResNet-50, batch 256, 5opt round: all 29 layer shapes at the stated batch -----------
+@pytest.mark.parametrize("layer", S.config2(), ids=lambda l: l.name)
+def test_config2_resnet50_batch_256(sq, oracle, layer):
+    """Every layer at batch 256 (input up to 205 MB, fp32 output up to 822 MB), with the kernel and tiling the
+    benchmark launches for it; the oracle recomputes 4096 and more sampled rows."""
+    assert layer.B == 256
+    assert_plan_is_the_benchmarks(sq, "cfg2", layer)
     check_sampled(sq, oracle, 2, layer, n=4096)
 
 
-@pytest.mark.parametrize("layer", [replace(l, B=8) for l in _C2 if l.name not in _C2_FULL], ids=lambda l: l.name)
-def test_config2_resnet50_other_layers_small_batch(sq, oracle, layer):
-    check_sampled(sq, oracle, 2, layer, n=512)
-
-
 # ---- config 3: the option sweep on M=65536, K=4608, N=512 ------------------------------------------
-@pytest.mark.parametrize("zf,modes", [(0.5, [S.Mode(4, S.OPT5, 1, 1), S.Mode(4, S.OPT5, 0, 0)]),
+@pytest.mark.parametrize("zf,modes", [(0.5, [S.Mode(4, S.OPT5, 0, 0)]),
                                       (0.2, [S.Mode(4, S.OPT3, 0, 1)]),
                                       (0.8, [S.Mode(4, S.OPT2, 1, 0)])], ids=["zf0.5", "zf0.2", "zf0.8"])
 def test_config3_full_size(sq, oracle, zf, modes):
     check_sampled(sq, oracle, 3, replace(S.config3_layer(), zf=zf), n=4096, modes=modes)
 
 
-def test_config3_full_size_as_convolution(sq, oracle):
-    """The same M, K, N as a 3x3 convolution over 512 channels (the form bench.py also times)."""
+def test_config3_full_size_every_output(sq, oracle):
+    """The materialised A[M,K] form at the benchmark's mode: all 65536 x 512 results against the oracle."""
+    layer = S.config3_layer()
+    assert_plan_is_the_benchmarks(sq, "cfg3", layer)
+    check_sampled(sq, oracle, 3, layer, full=True)
+
+
+def test_config3_full_size_as_convolution_every_output(sq, oracle):
+    """The same M, K, N as a 3x3 convolution over 512 channels (the benchmark's default workload): all
+    65536 x 512 results against the oracle."""
     layer = replace(S.config3_layer(), name="conv3x3_512_512_32x32", B=64, H=32, W=32, C=512, KH=3, KW=3, pad=(1, 1))
-    check_sampled(sq, oracle, 3, layer, n=4096)
+    assert_plan_is_the_benchmarks(sq, "cfg3-conv", layer)
+    check_sampled(sq, oracle, 3, layer, full=True)
 
 
 @pytest.mark.parametrize("mode,zf", S.config3_sweep(), ids=lambda v: v.label if isinstance(v, S.Mode) else f"zf{v}")
@@ -141,6 +182,7 @@ def test_config3_full_size_as_convolution_low_bit(sq, oracle):
 def test_config4_inception_4bit_and_2bit(sq, oracle, layer):
     """Both passes of the workload on the same tensors: 4-bit 5opt rounding, then the 2-bit window
     with 7 shifts where a zero partner grants 4 bits."""
+    assert_plan_is_the_benchmarks(sq, "cfg4", layer)
     check_sampled(sq, oracle, 4, layer, n=512, modes=[layer.mode, S.Mode(2, S.OPT7_2B, 1, 1)])
 
 
