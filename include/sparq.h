@@ -124,6 +124,25 @@ sparq_status sparq_conv_gemm(const uint8_t *x, const void *packed_w,
                              int32_t *acc, const float *scale, float *out,
                              void *workspace, size_t workspace_bytes, void *stream);
 
+/* sparq_conv_gemm for callers that cannot allocate device memory or carry a
+ * workspace around: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments and results as
+ * sparq_conv_gemm without the workspace: whatever scratch the layer needs (the
+ * channel-padded copy, split-reduction sums) is taken from an array inside the
+ * library's device image, SPARQ_STATIC_WORKSPACE_BYTES per GPU, held from the
+ * library's first use on that GPU until the process ends.  A layer whose
+ * sparq_workspace_bytes() exceeds that size returns SPARQ_EWORKSPACE before
+ * anything is launched.  The call allocates and frees nothing (no hipMalloc,
+ * no hipFree, no allocating library routine); its first call on a device
+ * looks the array's address up once.  All calls on one GPU share the one
+ * array: calls that may overlap on a GPU (different streams, different
+ * threads) race on it and must be ordered by the caller. */
+#define SPARQ_STATIC_WORKSPACE_BYTES (64u << 20)
+sparq_status sparq_conv_gemm_static_ws(const uint8_t *x, const void *packed_w,
+                                       const sparq_conv_desc *desc, const sparq_mode *mode,
+                                       int32_t *acc, const float *scale, float *out,
+                                       void *stream);
+
 /* Per-output-channel dequantisation (Section 5): out[m][n] = (float)acc[m][n] * scale[n]. */
 sparq_status sparq_dequant(const int32_t *acc, const float *scale, float *out,
                            int64_t M, int32_t N, void *stream);

@@ -5,10 +5,10 @@ below are the C entry points, taking torch device tensors as plain buffers.
 """
 from .binding import (  # noqa: F401
     LIB_PATH, SparqConvDesc, SparqError, SparqMode, conv_desc, lib, mode, out_rows, strerror,
-    sparq_conv_gemm, sparq_conv_gemm_u8, sparq_conv_plan, sparq_dequant, sparq_pack_weights, sparq_packed_bytes,
+    sparq_conv_gemm, sparq_conv_gemm_static_ws, sparq_conv_gemm_u8, sparq_conv_plan, sparq_dequant, sparq_pack_weights, sparq_packed_bytes,
     sparq_requant, sparq_trim, sparq_workspace_bytes,
 )
 
 __all__ = ["LIB_PATH", "SparqConvDesc", "SparqError", "SparqMode", "conv_desc", "lib", "mode", "out_rows",
-           "strerror", "sparq_conv_gemm", "sparq_conv_gemm_u8", "sparq_conv_plan", "sparq_dequant", "sparq_pack_weights",
+           "strerror", "sparq_conv_gemm", "sparq_conv_gemm_static_ws", "sparq_conv_gemm_u8", "sparq_conv_plan", "sparq_dequant", "sparq_pack_weights",
            "sparq_packed_bytes", "sparq_requant", "sparq_trim", "sparq_workspace_bytes"]

@@ -54,6 +54,8 @@ def _load() -> ctypes.CDLL:
     L.sparq_conv_plan.restype = ctypes.c_int
     L.sparq_conv_gemm.argtypes = [vp, vp, pd, pm, vp, vp, vp, vp, sz, vp]
     L.sparq_conv_gemm.restype = ctypes.c_int
+    L.sparq_conv_gemm_static_ws.argtypes = [vp, vp, pd, pm, vp, vp, vp, vp]
+    L.sparq_conv_gemm_static_ws.restype = ctypes.c_int
     L.sparq_dequant.argtypes = [vp, vp, vp, i64, i32, vp]
     L.sparq_dequant.restype = ctypes.c_int
     L.sparq_conv_gemm_u8.argtypes = [vp, vp, pd, pm, vp, vp, pm, vp, sz, vp]
@@ -152,6 +154,24 @@ def sparq_conv_gemm(x: torch.Tensor, packed: torch.Tensor, d: SparqConvDesc, m: 
     _check(lib.sparq_conv_gemm(_dev(x, torch.uint8, "x"), _dev(packed, torch.uint8, "packed"), ctypes.byref(d),
                                ctypes.byref(m), _dev(acc, torch.int32, "acc"), _dev(scale, torch.float32, "scale"),
                                _dev(out, torch.float32, "out"), ws_ptr, ws_bytes, _stream()), "sparq_conv_gemm")
+
+
+def sparq_conv_gemm_static_ws(x: torch.Tensor, packed: torch.Tensor, d: SparqConvDesc, m: SparqMode,
+                              acc: Optional[torch.Tensor] = None, scale: Optional[torch.Tensor] = None,
+                              out: Optional[torch.Tensor] = None) -> None:
+    """sparq_conv_gemm with its scratch taken from the library's own per-GPU array (nothing is allocated)."""
+    if x.numel() != d.B * d.H * d.W * d.C:
+        raise ValueError("activation size does not match the descriptor")
+    M = out_rows(d)
+    for t, nm in ((acc, "acc"), (out, "out")):
+        if t is not None and t.numel() != M * d.N:
+            raise ValueError(f"{nm} must hold M*N = {M * d.N} elements")
+    if scale is not None and scale.numel() != d.N:
+        raise ValueError("scale must hold N elements")
+    _check(lib.sparq_conv_gemm_static_ws(_dev(x, torch.uint8, "x"), _dev(packed, torch.uint8, "packed"), ctypes.byref(d),
+                                         ctypes.byref(m), _dev(acc, torch.int32, "acc"),
+                                         _dev(scale, torch.float32, "scale"), _dev(out, torch.float32, "out"), _stream()),
+           "sparq_conv_gemm_static_ws")
 
 
 def sparq_dequant(acc: torch.Tensor, scale: torch.Tensor, out: torch.Tensor) -> None:

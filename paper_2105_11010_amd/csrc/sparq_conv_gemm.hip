@@ -409,6 +409,53 @@ extern "C" sparq_status sparq_conv_gemm(const uint8_t* x, const void* packed_w, 
     return conv_launch(x, packed_w, desc, mode, acc, scale, out, nullptr, nullptr, workspace, workspace_bytes, stream);
 }
 
+// ---- the same convolution for callers that cannot allocate: the scratch lives in the library's own image ----
+// One array per device (every GPU the library's code object is loaded on holds its own copy at its own
+// address, until the process ends).  In host code the array's name is only a handle for the symbol lookup:
+// the device address comes from hipGetSymbolAddress, once per device, and is what the kernels are given.
+static __device__ __align__(256) unsigned char scratch[SPARQ_STATIC_WORKSPACE_BYTES];
+
+namespace {
+sparq_status static_scratch_address(void** ptr) {
+    static void* addr[kMaxDevices] = {};
+    static std::mutex mu;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0) return SPARQ_ELAUNCH;
+    std::lock_guard<std::mutex> lock(mu);
+    if (dev < kMaxDevices && addr[dev]) {
+        *ptr = addr[dev];
+        return SPARQ_OK;
+    }
+    void* a = nullptr;
+    if (hipGetSymbolAddress(&a, HIP_SYMBOL(scratch)) != hipSuccess || !a) {
+        (void)hipGetLastError();
+        return SPARQ_ELAUNCH;
+    }
+    if (dev < kMaxDevices) addr[dev] = a;       // ordinals past the table look the address up on every call
+    *ptr = a;
+    return SPARQ_OK;
+}
+}  // namespace
+
+extern "C" sparq_status sparq_conv_gemm_static_ws(const uint8_t* x, const void* packed_w, const sparq_conv_desc* desc,
+                                                  const sparq_mode* mode, int32_t* acc, const float* scale, float* out,
+                                                  void* stream) {
+    if (!acc && !out) return SPARQ_EINVAL;
+    ConvGeom g;
+    if (!conv_geom(desc, &g) || !mode_valid(mode)) return SPARQ_EINVAL;
+    const ConvPlan pl = make_plan(g);
+    const size_t need = pl.pad_bytes + pl.split_bytes;
+    if (need > (size_t)SPARQ_STATIC_WORKSPACE_BYTES) return SPARQ_EWORKSPACE;
+    void* ws = nullptr;
+    if (need) {
+        const sparq_status st = static_scratch_address(&ws);
+        if (st != SPARQ_OK) return st;
+    }
+    // Every byte of the scratch a call reads it has written itself first (the padded copy is written whole by the
+    // trim pass, split sums are cleared by a kernel), so the last call's contents never show.
+    return conv_launch(x, packed_w, desc, mode, acc, scale, out, nullptr, nullptr, ws, need, stream);
+}
+
 extern "C" sparq_status sparq_conv_gemm_u8(const uint8_t* x, const void* packed_w, const sparq_conv_desc* desc,
                                            const sparq_mode* mode, const float* factor, uint8_t* y,
                                            const sparq_mode* out_mode, void* workspace, size_t workspace_bytes,

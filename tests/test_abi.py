@@ -26,7 +26,7 @@ def lib():
 
 
 def test_header_declares_the_boundary():
-    assert declared_symbols() == ["sparq_conv_gemm", "sparq_conv_gemm_u8", "sparq_conv_plan", "sparq_dequant", "sparq_pack_weights",
+    assert declared_symbols() == ["sparq_conv_gemm", "sparq_conv_gemm_static_ws", "sparq_conv_gemm_u8", "sparq_conv_plan", "sparq_dequant", "sparq_pack_weights",
                                   "sparq_packed_bytes", "sparq_requant", "sparq_strerror", "sparq_trim", "sparq_workspace_bytes"]
 
 
