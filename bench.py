@@ -27,14 +27,34 @@ if ROOT not in sys.path:
 PEAK_INT8_TOPS = 5000.0     # MI355X dense int8 MFMA, published
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E, published
 
-# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of
-# this script (summary under profiles/).  FETCH_SIZE reads half the true figure on this
-# chip (calibrated on the trim kernel, which reads and writes exactly the tensor's size), WRITE_SIZE
-# reads true KiB; the figures below are already scaled.
-MEASURED_TRAFFIC = {
-    "cfg3-conv": {"fetch_bytes": 128_260_000, "write_bytes": 134_220_000},
-    "cfg3": {"fetch_bytes": 346_910_000, "write_bytes": 139_200_000},
-}
+# HBM bytes per launch of the dominant kernel come from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of this
+# script; their summary is committed as profiles/conv_cfg3_hbm_traffic.md and carries one machine-readable line per
+# workload ("traffic <workload> fetch_bytes=<n> write_bytes=<n>", already scaled by the copy-kernel calibration).
+TRAFFIC_PROFILE = os.path.join("profiles", "conv_cfg3_hbm_traffic.md")
+
+
+def measured_traffic(workload):
+    """{"fetch_bytes", "write_bytes"} of `workload` from the committed counter summary, or None."""
+    import re
+    try:
+        text = open(os.path.join(ROOT, TRAFFIC_PROFILE)).read()
+    except OSError:
+        return None
+    m = re.search(rf"^traffic {re.escape(workload)} fetch_bytes=(\d+) write_bytes=(\d+)\s*$", text, re.M)
+    return {"fetch_bytes": int(m.group(1)), "write_bytes": int(m.group(2))} if m else None
+
+
+def layer_bounds(layer, out_bytes=4):
+    """Lower bounds of one launch of `layer` against the published peaks: (ms at the int8 matrix peak, ms at the
+    HBM peak on the algorithmic bytes = input once + weights + results)."""
+    x_b = layer.B * layer.H * layer.W * layer.C
+    alg = x_b + layer.K * layer.N + out_bytes * layer.M * layer.N
+    return layer.ops / (PEAK_INT8_TOPS * 1e12) * 1e3, alg / (PEAK_HBM_GBPS * 1e9) * 1e3
+
+
+def table_bound_ms(layers, out_bytes=4):
+    """Sum over a layer table of max(matrix bound, HBM bound): no schedule of these launches can be faster."""
+    return sum(max(layer_bounds(l, out_bytes)) * l.repeat for l in layers)
 
 
 def parse_args():
@@ -60,6 +80,7 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-layer", action="store_true", help="print a per-layer table on stderr")
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary figures of the default run")
+    ap.add_argument("--no-probes", action="store_true", help="skip the machine-ceiling probes and the zero-operand run")
     ap.add_argument("--sweep-bits", default="4", choices=["4", "low"],
                     help="cfg3-sweep: the 36 points of the 4-bit option sets (default) or the 24 points of the 3-bit / 6-shift "
                          "and 2-bit / 7-shift variants")
@@ -223,6 +244,81 @@ def sweep(args, sq, S, torch, dev):
         "points": points, "roofline": None, "cpu_baseline": None}), flush=True)
 
 
+def time_calls(torch, fn, warm, reps):
+    """ms per call of fn(i), HIP events on the current (launch) stream."""
+    for i in range(warm):
+        fn(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(reps):
+        fn(i)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def machine_probes(torch, dev):
+    """Ceilings measured on this device (include/sparq_probe.h): the int8 matrix instruction on register operands with
+    all-zero and with random operand bytes, and a streaming copy over 1 GiB (far larger than the last-level cache)."""
+    import numpy as np
+    from paper_2105_11010_amd import probe as P
+    iters = 4000
+    sink = torch.empty(P.SINK_BYTES, dtype=torch.uint8, device=dev)
+    rng = np.random.Generator(np.random.PCG64(7))
+    res = {}
+    for name, host in (("zero_operands", np.zeros(P.OPERAND_BYTES, dtype=np.uint8)),
+                       ("random_operands", rng.integers(0, 256, P.OPERAND_BYTES, dtype=np.uint8))):
+        ops = torch.from_numpy(host).to(dev)
+        ms = time_calls(torch, lambda i: P.sparq_probe_mfma_i8(ops, sink, iters), 3, 10)
+        res[name] = round(P.sparq_probe_mfma_i8_ops(iters) / ms / 1e9, 1)
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 256)
+    dst = torch.empty(n, dtype=torch.uint8, device=dev)
+    ms = time_calls(torch, lambda i: P.sparq_probe_copy(src, dst), 2, 10)
+    del src, dst
+    torch.cuda.empty_cache()
+    return {"int8_mfma_TOPS": res, "copy_GBps": round(2 * n / ms / 1e6, 1),
+            "note": "v_mfma_i32_32x32x32_i8 on register operands, one wavefront per SIMD (its rate depends on the operand "
+                    "data: the chip lowers its clock under the power the multipliers draw); copy: 1 GiB read + 1 GiB written"}
+
+
+def streaming_kernels(sq, S, torch, dev, dom, reps):
+    """Standalone trim and dequantisation kernels, HBM-bound.  'cold': on config 3's materialised A (302 MB in, 302 MB
+    out per call) / on three rotating 134 MB accumulator tensors -- more than the 256 MB last-level cache holds, so every
+    byte comes from and goes to HBM; 'warm': on the dominant layer's own input (33.5 MB), which stays cache-resident."""
+    import numpy as np
+    out = {}
+    xin = dom["x"]
+    y = torch.empty_like(xin)
+    ms = time_calls(torch, lambda i: sq.sparq_trim(xin, y, dom["m"]), 2, reps)
+    warm = {"GBps": round(2 * xin.numel() / ms / 1e6, 1), "bytes_per_launch": 2 * xin.numel(), "ms": round(ms, 4)}
+    del y
+    big = S.config3_layer()                      # A[65536][4608]
+    rng = S.rng_for(3, 77)
+    block = S.gen_activations((1 << 24,), big.zf, rng)
+    xa = torch.from_numpy(np.resize(block, (big.M, big.K))).to(dev)
+    ya = torch.empty_like(xa)
+    ms = time_calls(torch, lambda i: sq.sparq_trim(xa, ya, dom["m"]), 2, reps)
+    cold = {"GBps": round(2 * xa.numel() / ms / 1e6, 1), "bytes_per_launch": 2 * xa.numel(), "ms": round(ms, 4)}
+    del xa, ya
+    out["trim"] = {"GBps": cold["GBps"], "frac_hbm_peak": round(cold["GBps"] / PEAK_HBM_GBPS, 4), "state": "cold (HBM)",
+                   "tensor": "config 3 A[65536][4608] uint8", "bytes_per_launch": cold["bytes_per_launch"], "ms": cold["ms"],
+                   "warm_cache_resident": dict(warm, tensor="the dominant layer's input")}
+    L = dom["layer"]
+    accs = [torch.randint(-2 ** 24, 2 ** 24, (L.M, L.N), dtype=torch.int32, device=dev) for _ in range(3)]
+    outs = [torch.empty((L.M, L.N), dtype=torch.float32, device=dev) for _ in range(3)]
+    ms_cold = time_calls(torch, lambda i: sq.sparq_dequant(accs[i % 3], dom["sc"], outs[i % 3]), 3, reps)
+    ms_warm = time_calls(torch, lambda i: sq.sparq_dequant(accs[0], dom["sc"], outs[0]), 2, reps)
+    nbytes = 8 * accs[0].numel()
+    out["dequant"] = {"GBps": round(nbytes / ms_cold / 1e6, 1), "frac_hbm_peak": round(nbytes / ms_cold / 1e6 / PEAK_HBM_GBPS, 4),
+                      "state": "cold (HBM): three rotating tensor pairs, 805 MB", "bytes_per_launch": nbytes, "ms": round(ms_cold, 4),
+                      "warm_one_pair": {"GBps": round(nbytes / ms_warm / 1e6, 1), "ms": round(ms_warm, 4)}}
+    del accs, outs
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -248,101 +344,95 @@ def main():
     items = prepare(sq, S, torch, dev, cfg_id, layers, keep_host=len(layers) == 1, outputs=(args.output,))
     print(f"[bench] inputs generated and uploaded in {time.time() - t_gen:.1f}s", file=sys.stderr, flush=True)
 
+    # ---- the machine's own ceilings, measured first (they also take the chip out of its idle clocks) ----
+    probes = None if args.no_probes else machine_probes(torch, dev)
+
+    # ---- W untimed steps, then exactly K timed steps ----
     ms_per_step, wall_ms = time_steps(sq, torch, items, args.warmup, args.steps, args.output)
     total_ops = S.total_ops(layers)
     tops = total_ops / (ms_per_step * 1e-3) / 1e12
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    out_bytes = 4 if args.output == "fp32" else 1
 
     # ---- dominant kernel: the fused conv-GEMM of the largest layer, timed on its own ----
     dom = max(items, key=lambda it: it["layer"].ops * it["layer"].repeat)
     reps = max(5, args.steps)
-    for _ in range(2):
-        run_layer(sq, dom, args.output)
-    torch.cuda.synchronize()
-    e0.record()
-    for _ in range(reps):
-        run_layer(sq, dom, args.output)
-    e1.record()
-    torch.cuda.synchronize()
-    dom_ms = e0.elapsed_time(e1) / reps
+    if len(items) == 1 and dom["layer"].repeat == 1:
+        dom_ms = ms_per_step                     # a one-layer workload: the timed region is this kernel's launches
+    else:
+        dom_ms = time_calls(torch, lambda i: run_layer(sq, dom, args.output), 2, reps)
     dom_tops = dom["layer"].ops / (dom_ms * 1e-3) / 1e12
-    tr = MEASURED_TRAFFIC.get(args.workload) if (args.rows == 65536 and args.mask is None and args.round is None
-                                                 and args.pair is None and args.zf is None and args.output == "fp32") else None
+    default_point = (args.rows == 65536 and args.mask is None and args.round is None and args.pair is None
+                     and args.zf is None and args.output == "fp32")
+    tr = measured_traffic(args.workload) if default_point else None
     x_b, w_b = dom["x"].numel(), dom["layer"].K * dom["layer"].N
+    b_mfma, b_hbm = layer_bounds(dom["layer"], out_bytes)
     roofline = {"bound": "mfma", "achieved": round(dom_tops, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
                 "frac": round(dom_tops / PEAK_INT8_TOPS, 4),
                 "traffic": (tr["fetch_bytes"] + tr["write_bytes"]) if tr else None,
-                "traffic_detail": tr,
-                "algorithmic_bytes": x_b + w_b + (4 if args.output == "fp32" else 1) * dom["layer"].M * dom["layer"].N,
+                "traffic_detail": tr, "traffic_source": TRAFFIC_PROFILE if tr else None,
+                "algorithmic_bytes": x_b + w_b + out_bytes * dom["layer"].M * dom["layer"].N,
                 "kernel": sq.sparq_conv_plan(dom["d"], dom["m"]), "layer": dom["layer"].name, "ms_per_launch": round(dom_ms, 4),
-                "ops_per_launch": dom["layer"].ops}
+                "ops_per_launch": dom["layer"].ops,
+                "bound_ms": {"mfma": round(b_mfma, 4), "hbm": round(b_hbm, 4), "min_time": round(max(b_mfma, b_hbm), 4)}}
+    if probes:
+        roofline["peak_measured"] = probes
+        roofline["frac_of_measured_random_operand_peak"] = round(dom_tops / probes["int8_mfma_TOPS"]["random_operands"], 4)
+    if len(layers) == 1 and args.output == "fp32" and not args.no_probes:
+        # The same kernel, the same launch, all-zero activations and weights: the instruction stream is identical,
+        # only the operand bytes differ -- what is left of the difference is the chip's data-dependent clock.
+        L = dom["layer"]
+        xz = torch.zeros_like(dom["x"])
+        wz = torch.zeros(L.w_shape(), dtype=torch.int8, device=dev)
+        pz = torch.empty_like(dom["packed"])
+        sq.sparq_pack_weights(wz, dom["d"], pz)
+        zero_it = dict(dom, x=xz, packed=pz)
+        z_ms = time_calls(torch, lambda i: run_layer(sq, zero_it, args.output), max(2, args.warmup), reps)
+        roofline["same_kernel_zero_operands"] = {"TOPS": round(L.ops / z_ms / 1e9, 2), "frac": round(L.ops / z_ms / 1e9 / PEAK_INT8_TOPS, 4),
+                                                 "ms_per_launch": round(z_ms, 4)}
+        del xz, wz, pz, zero_it
 
-    # ---- standalone trim and dequant kernels (HBM-bound), on the dominant layer's tensors ----
-    xin = dom["x"]
-    y = torch.empty_like(xin)
-    for _ in range(2):
-        sq.sparq_trim(xin, y, dom["m"])
-    torch.cuda.synchronize()
-    e0.record()
-    for _ in range(reps):
-        sq.sparq_trim(xin, y, dom["m"])
-    e1.record()
-    torch.cuda.synchronize()
-    trim_ms = e0.elapsed_time(e1) / reps
-    trim_gbps = 2 * xin.numel() / (trim_ms * 1e-3) / 1e9
-    del y
-    acc = torch.randint(-2 ** 24, 2 ** 24, (dom["layer"].M, dom["layer"].N), dtype=torch.int32, device=dev)
-    deq_out = dom["out"] if dom["out"] is not None else torch.empty(acc.shape, dtype=torch.float32, device=dev)
-    for _ in range(2):
-        sq.sparq_dequant(acc, dom["sc"], deq_out)
-    torch.cuda.synchronize()
-    e0.record()
-    for _ in range(reps):
-        sq.sparq_dequant(acc, dom["sc"], deq_out)
-    e1.record()
-    torch.cuda.synchronize()
-    deq_ms = e0.elapsed_time(e1) / reps
-    deq_gbps = 8 * acc.numel() / (deq_ms * 1e-3) / 1e9
-    del acc, deq_out
+    # ---- standalone trim and dequant kernels (HBM-bound) ----
+    stream = streaming_kernels(sq, S, torch, dev, dom, reps)
 
     if args.per_layer:
-        print(f"{'layer':28s} {'M':>8s} {'K':>6s} {'N':>5s} {'rep':>3s} {'ms':>9s} {'TOPS':>8s}", file=sys.stderr)
+        print(f"{'layer':28s} {'M':>8s} {'K':>6s} {'N':>5s} {'rep':>3s} {'ms':>9s} {'TOPS':>8s} {'mfma ms':>8s} {'hbm ms':>8s} "
+              f"{'bound':>5s} {'frac':>6s}", file=sys.stderr)
         for it in items:
             L = it["layer"]
-            run_layer(sq, it, args.output)
-            torch.cuda.synchronize()
-            e0.record()
-            for _ in range(10):
-                run_layer(sq, it, args.output)
-            e1.record()
-            torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / 10
-            print(f"{L.name:28s} {L.M:8d} {L.K:6d} {L.N:5d} {L.repeat:3d} {ms:9.4f} {L.ops / ms / 1e9:8.1f}",
-                  file=sys.stderr)
+            ms = time_calls(torch, lambda i: run_layer(sq, it, args.output), 1, 10)
+            bm, bh = layer_bounds(L, out_bytes)
+            print(f"{L.name:28s} {L.M:8d} {L.K:6d} {L.N:5d} {L.repeat:3d} {ms:9.4f} {L.ops / ms / 1e9:8.1f} {bm:8.4f} {bh:8.4f} "
+                  f"{'mfma' if bm >= bh else 'hbm':>5s} {max(bm, bh) / ms:6.3f}", file=sys.stderr)
 
     # ---- secondary figures of the default run: the same GEMM with a materialised A[M,K] (no reuse
     #      between filter taps), the ResNet-18 layer table (small layers that do not fill the chip)
-    #      and the Inception-shaped table ----
+    #      and the Inception-shaped table; each with the sum of its layers' lower bounds ----
     also = None
     if args.workload == "cfg3-conv" and not args.no_extra and args.rows == 65536:
         also = []
+
+        def entry(name, layers_, ms, ob):
+            bound = table_bound_ms(layers_, ob)
+            return {"workload": name, "value": round(S.total_ops(layers_) / ms / 1e9, 2), "unit": "TOPS", "ms_per_step": round(ms, 4),
+                    "total_gop": round(S.total_ops(layers_) / 1e9, 3),
+                    "bound_ms": {"mfma": round(sum(layer_bounds(l, ob)[0] * l.repeat for l in layers_), 4),
+                                 "hbm": round(sum(layer_bounds(l, ob)[1] * l.repeat for l in layers_), 4),
+                                 "sum_of_per_layer_max": round(bound, 4)},
+                    "frac_of_bound": round(bound / ms, 4)}
+
         for wl in ("cfg3", "cfg1", "cfg4"):
             a2 = argparse.Namespace(**{**vars(args), "workload": wl})
             c2, l2, n2 = build_workload(a2)
             it2 = prepare(sq, S, torch, dev, c2, l2, outputs=("fp32", "u8", "u8-chain") if wl != "cfg3" else ("fp32",))
             ms2, _ = time_steps(sq, torch, it2, args.warmup, args.steps)
-            also.append({"workload": n2, "value": round(S.total_ops(l2) / ms2 / 1e9, 2), "unit": "TOPS",
-                         "ms_per_step": round(ms2, 4), "total_gop": round(S.total_ops(l2) / 1e9, 3)})
+            also.append(entry(n2, l2, ms2, 4))
             if wl != "cfg3":
                 # the same table with every result requantised to uint8 (one byte per output instead of four)
                 ms3, _ = time_steps(sq, torch, it2, args.warmup, args.steps, "u8")
-                also.append({"workload": n2 + ", uint8 requantised outputs", "value": round(S.total_ops(l2) / ms3 / 1e9, 2),
-                             "unit": "TOPS", "ms_per_step": round(ms3, 4), "total_gop": round(S.total_ops(l2) / 1e9, 3)})
+                also.append(entry(n2 + ", uint8 requantised outputs", l2, ms3, 1))
                 # and as the layers of a chained network: trimmed once, in the producer's epilogue
                 ms4, _ = time_steps(sq, torch, it2, args.warmup, args.steps, "u8-chain")
-                also.append({"workload": n2 + ", chained (input arrives trimmed; uint8 output trimmed for the next layer)",
-                             "value": round(S.total_ops(l2) / ms4 / 1e9, 2), "unit": "TOPS", "ms_per_step": round(ms4, 4),
-                             "total_gop": round(S.total_ops(l2) / 1e9, 3)})
+                also.append(entry(n2 + ", chained (input arrives trimmed; uint8 output trimmed for the next layer)", l2, ms4, 1))
             del it2
             torch.cuda.empty_cache()
 
@@ -391,13 +481,12 @@ def main():
         "config": {"workload": wl_name, "layers": sum(l.repeat for l in layers), "total_gop": round(total_ops / 1e9, 3),
                    "output": {"fp32": "fp32 (fused dequant)", "u8": "uint8 (fused requantisation)",
                               "u8-chain": "uint8 (fused requantisation + the next layer's trim; input arrives trimmed)"}[args.output],
-                   "wall_ms_per_step": round(wall_ms, 4)},
+                   "wall_ms_per_step": round(wall_ms, 4),
+                   "bound_ms_per_step": round(table_bound_ms(layers, out_bytes), 4)},
         "pct_int8_mfma_peak": round(100 * tops / PEAK_INT8_TOPS, 2),
         "roofline": roofline,
-        "trim": {"GBps": round(trim_gbps, 1), "frac_hbm_peak": round(trim_gbps / PEAK_HBM_GBPS, 4),
-                 "bytes_per_launch": 2 * xin.numel(), "ms": round(trim_ms, 4)},
-        "dequant": {"GBps": round(deq_gbps, 1), "frac_hbm_peak": round(deq_gbps / PEAK_HBM_GBPS, 4),
-                    "ms": round(deq_ms, 4)},
+        "trim": stream["trim"],
+        "dequant": stream["dequant"],
         "cpu_baseline": cpu,
     }
     if also:

@@ -8,6 +8,8 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsparq.so")
+PROBE_SRC = os.path.join(CSRC, "probe", "sparq_probe.hip")
+PROBE_LIB = os.path.join(HERE, "libsparq_probe.so")   # machine-ceiling micro-benchmarks (include/sparq_probe.h)
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
@@ -21,7 +23,7 @@ def sources():
 
 
 def build(verbose: bool = False, jobs: int = 8) -> str:
-    """Compile every .hip under csrc/ and link libsparq.so. Always recompiles."""
+    """Compile every .hip under csrc/ and link libsparq.so, then libsparq_probe.so. Always recompiles."""
     objs = []
 
     def compile_one(src):
@@ -42,6 +44,9 @@ def build(verbose: bool = False, jobs: int = 8) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
+    r = subprocess.run([HIPCC, *FLAGS, "-shared", PROBE_SRC, "-o", PROBE_LIB], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed on {PROBE_SRC}:\n{r.stdout}\n{r.stderr}")
     return LIB
 
 

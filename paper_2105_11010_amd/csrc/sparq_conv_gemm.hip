@@ -63,25 +63,25 @@ const PatchVariant kPatchVariants[] = {
 // image with period lcm(128, Ho*Wo), so one period plus the last tile is an exact walk; results
 // are cached because the same layers are launched over and over.
 int patch_npix_max(const PatchGeom& g) {
-    struct Key { int v[12]; int npix; };
+    struct Key { int v[13]; int npix; };
     static Key cache[64];
     static int used = 0, next = 0;
     static std::mutex mu;
-    const int key[12] = {g.M, g.B, g.H, g.W, g.KH, g.KW, g.sh, g.sw, g.ph, g.pw, g.Ho, g.Wo};
+    const int key[13] = {g.tm, g.M, g.B, g.H, g.W, g.KH, g.KW, g.sh, g.sw, g.ph, g.pw, g.Ho, g.Wo};
     std::lock_guard<std::mutex> lock(mu);
     for (int i = 0; i < used; ++i)
         if (!memcmp(cache[i].v, key, sizeof(key))) return cache[i].npix;
     const int64_t img = (int64_t)g.Ho * g.Wo;
-    int64_t a = kPatchTM, b = img;
+    int64_t a = g.tm, b = img;
     while (b) { const int64_t t = a % b; a = b; b = t; }
     const int64_t period_tiles = img / a;                       // lcm(TM, img) / TM
-    const int64_t tiles = ((int64_t)g.M + kPatchTM - 1) / kPatchTM;
+    const int64_t tiles = ((int64_t)g.M + g.tm - 1) / g.tm;
     int npix = 0;
     for (int64_t t = 0; t < tiles && t <= period_tiles; ++t) {
-        const int n = tile_patch(g, (int)(t * kPatchTM)).npix;
+        const int n = tile_patch(g, (int)(t * g.tm)).npix;
         npix = n > npix ? n : npix;
     }
-    const int n_last = tile_patch(g, (int)((tiles - 1) * kPatchTM)).npix;
+    const int n_last = tile_patch(g, (int)((tiles - 1) * g.tm)).npix;
     npix = n_last > npix ? n_last : npix;
     Key& slot = cache[used < 64 ? used++ : (next++ & 63)];
     memcpy(slot.v, key, sizeof(key));
@@ -89,15 +89,25 @@ int patch_npix_max(const PatchGeom& g) {
     return npix;
 }
 
-// Fills `pg`, `npix`, and picks staging (chunks per lane, channel block); false: not eligible.
-bool plan_patch(const ConvGeom& g, PatchGeom* pg, int* npix, int* ac, int* cbs) {
+// The patch geometry of `g` for tiles of `tm` output pixels and the largest patch; false: outside what the
+// index arithmetic of the input-patch kernels covers.
+bool patch_geom_for(const ConvGeom& g, int tm, PatchGeom* pg, int* npix) {
     if (g.Cq % kStepK != 0) return false;                        // fewer than 33 channels: taps are not step-aligned
     if (g.M >= kPatchMaxDividend || (size_t)g.Kp * g.Np >= kPatchInvalidOffset) return false;
     if ((int64_t)g.B * g.H * g.W >= kPatchMaxDividend) return false;     // the pixel remap of strided 1x1 layers
-    PatchGeom q = make_patch_geom(g.B, g.H, g.W, g.KH, g.KW, g.sh, g.sw, g.ph, g.pw);
+    PatchGeom q = make_patch_geom(g.B, g.H, g.W, g.KH, g.KW, g.sh, g.sw, g.ph, g.pw, tm);
     if ((int64_t)q.B * q.Hv + q.KH >= kPatchMaxDividend) return false;
     if (patch_npix_bound(q) > 4096) return false;               // far too large: skip the exact walk
-    const int n = patch_npix_max(q);
+    *npix = patch_npix_max(q);
+    *pg = q;
+    return true;
+}
+
+// Fills `pg`, `npix`, and picks staging (chunks per lane, channel block); false: not eligible.
+bool plan_patch(const ConvGeom& g, PatchGeom* pg, int* npix, int* ac, int* cbs) {
+    PatchGeom q;
+    int n;
+    if (!patch_geom_for(g, kPatchTM, &q, &n)) return false;
     const int taps = q.KH * q.KW;
     const int ksteps = g.Cq / kStepK;
     // candidates (chunks per lane, channel block / 64): larger channel blocks first for 1x1 layers,

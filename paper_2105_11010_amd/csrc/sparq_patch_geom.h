@@ -1,6 +1,6 @@
 // Index arithmetic of the input-patch convolution kernel, shared by device and host code.
 //
-// A tile is 128 consecutive output pixels in (b, oy, ox) order.  All input pixels that any
+// A tile is PatchGeom::tm (128 or 256) consecutive output pixels in (b, oy, ox) order.  All input pixels that any
 // filter tap of any of those outputs touches form a rectangle of "virtual rows" x columns:
 //
 //   virtual row  v = b * Hv + (iy + pad_h),  Hv = H + 2 * pad_h     (padding rows included)
@@ -24,11 +24,12 @@
 
 namespace sparq {
 
-constexpr int kPatchTM = 128;              // output pixels per tile
+constexpr int kPatchTM = 128;              // output pixels per tile (default; PatchGeom::tm is what counts)
 constexpr int kPatchMaxDividend = 1 << 22;
 
 struct PatchGeom {                          // per launch
     int M;                                  // B * Ho * Wo
+    int tm;                                 // output pixels per tile
     int B, H, W, Ho, Wo, KH, KW, sh, sw, ph, pw;
     int Hv;                                 // H + 2 * ph
     float rcp_wo, rcp_ho, rcp_hv;
@@ -74,8 +75,9 @@ SPARQ_GEOM_HD int remap_pixel(const PatchGeom& g, int m) {
 
 // The geometry the patch kernel runs a convolution with (set-up shared by the library and its host test).
 // 1x1 filters without padding become one long row (with a pixel remap when strided).
-inline PatchGeom make_patch_geom(int B, int H, int W, int KH, int KW, int sh, int sw, int ph, int pw) {
+inline PatchGeom make_patch_geom(int B, int H, int W, int KH, int KW, int sh, int sw, int ph, int pw, int tm = kPatchTM) {
     PatchGeom q{};
+    q.tm = tm;
     const int Ho = (H + 2 * ph - KH) / sh + 1, Wo = (W + 2 * pw - KW) / sw + 1;
     const int M = B * Ho * Wo;
     if (KH == 1 && KW == 1 && ph == 0 && pw == 0) {
@@ -106,7 +108,7 @@ SPARQ_GEOM_HD void out_pixel_origin(const PatchGeom& g, int m, int* v, int* x) {
 SPARQ_GEOM_HD TilePatch tile_patch(const PatchGeom& g, int m0) {
     TilePatch t;
     t.m0 = m0;
-    const int m1 = (m0 + kPatchTM - 1 < g.M - 1) ? m0 + kPatchTM - 1 : g.M - 1;
+    const int m1 = (m0 + g.tm - 1 < g.M - 1) ? m0 + g.tm - 1 : g.M - 1;
     int va, xa, vb, xb;
     out_pixel_origin(g, m0, &va, &xa);
     out_pixel_origin(g, m1, &vb, &xb);
@@ -130,14 +132,14 @@ SPARQ_GEOM_HD TilePatch tile_patch(const PatchGeom& g, int m0) {
 // Upper bound of TilePatch::npix over all tiles of a launch (closed form, no tile walk).
 inline int64_t patch_npix_bound(const PatchGeom& g) {
     const int64_t rows_total = (int64_t)g.B * g.Ho;
-    int64_t d = (kPatchTM - 2) / g.Wo + 1;                       // largest r1 - r0 of a tile
-    if (g.M <= 1 || kPatchTM == 1) d = 0;
+    int64_t d = (g.tm - 2) / g.Wo + 1;                           // largest r1 - r0 of a tile
+    if (g.M <= 1 || g.tm == 1) d = 0;
     if (d > rows_total - 1) d = rows_total - 1;
     if (g.Wo >= g.M) d = 0;
     const int64_t gap = g.Hv - (int64_t)g.Ho * g.sh > 0 ? g.Hv - (int64_t)g.Ho * g.sh : 0;   // unused virtual rows between images
     const int64_t crossings = (d + g.Ho - 1) / g.Ho;
     const int64_t nrows = d * g.sh + g.KH + crossings * gap;
-    int64_t single = (int64_t)(kPatchTM - 1) * g.sw + g.KW;      // widest one-row tile
+    int64_t single = (int64_t)(g.tm - 1) * g.sw + g.KW;          // widest one-row tile
     const int64_t full = (int64_t)(g.Wo - 1) * g.sw + g.KW;
     if (single > full) single = full;
     const int64_t pwt = d > 0 ? full : single;

@@ -2,7 +2,8 @@
 // convolution shape, every output pixel and every filter tap, the patch pixel the kernel would
 // read must hold exactly the input pixel the convolution's definition names (or padding), lie
 // inside the patch, and the patch must not exceed the closed-form size bound.
-//   usage: patch_geom_check B H W KH KW stride_h stride_w pad_h pad_w   -> prints "ok <tiles> <max npix> <bound>"
+// Both tile heights the kernels use (128 and 256 output pixels) are walked.
+//   usage: patch_geom_check B H W KH KW stride_h stride_w pad_h pad_w   -> prints "ok <tiles> <max npix> <bound>" (of the 128-pixel walk)
 #include <stdio.h>
 #include <stdlib.h>
 
@@ -10,21 +11,18 @@
 
 using namespace sparq;
 
-int main(int argc, char** argv) {
-    if (argc < 10) return 2;
-    const int B = atoi(argv[1]), H = atoi(argv[2]), W = atoi(argv[3]), KH = atoi(argv[4]), KW = atoi(argv[5]);
-    const int sh = atoi(argv[6]), sw = atoi(argv[7]), ph = atoi(argv[8]), pw = atoi(argv[9]);
-    const PatchGeom g = make_patch_geom(B, H, W, KH, KW, sh, sw, ph, pw);      // as the library sets it up
+static int walk(int B, int H, int W, int KH, int KW, int sh, int sw, int ph, int pw, int tm, bool report) {
+    const PatchGeom g = make_patch_geom(B, H, W, KH, KW, sh, sw, ph, pw, tm);      // as the library sets it up
     const int Ho = (H + 2 * ph - KH) / sh + 1, Wo = (W + 2 * pw - KW) / sw + 1;
     const int C = 16;
     const long long bound = patch_npix_bound(g);
     long long maxpix = 0;
     int tiles = 0;
-    for (int m0 = 0; m0 < g.M; m0 += kPatchTM, ++tiles) {
+    for (int m0 = 0; m0 < g.M; m0 += tm, ++tiles) {
         const TilePatch t = tile_patch(g, m0);
         if (t.npix > maxpix) maxpix = t.npix;
         if (t.npix > bound) { printf("FAIL bound: tile %d npix %d > %lld\n", tiles, t.npix, bound); return 1; }
-        for (int m = m0; m < m0 + kPatchTM && m < g.M; ++m) {
+        for (int m = m0; m < m0 + tm && m < g.M; ++m) {
             const int ox = m % Wo, oy = (m / Wo) % Ho, b = m / (Wo * Ho);
             const int base = patch_pixel_of_output(g, t, m);
             for (int kh = 0; kh < KH; ++kh)
@@ -42,6 +40,14 @@ int main(int argc, char** argv) {
         // pixels past the patch must decode as "nothing"
         if (patch_pixel_offset(g, t, t.npix, C) != -1) { printf("FAIL tail\n"); return 1; }
     }
-    printf("ok %d %lld %lld\n", tiles, maxpix, bound);
+    if (report) printf("ok %d %lld %lld\n", tiles, maxpix, bound);
     return 0;
+}
+
+int main(int argc, char** argv) {
+    if (argc < 10) return 2;
+    const int B = atoi(argv[1]), H = atoi(argv[2]), W = atoi(argv[3]), KH = atoi(argv[4]), KW = atoi(argv[5]);
+    const int sh = atoi(argv[6]), sw = atoi(argv[7]), ph = atoi(argv[8]), pw = atoi(argv[9]);
+    if (int rc = walk(B, H, W, KH, KW, sh, sw, ph, pw, 256, false)) return rc;
+    return walk(B, H, W, KH, KW, sh, sw, ph, pw, 128, true);
 }

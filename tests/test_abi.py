@@ -30,6 +30,25 @@ def test_header_declares_the_boundary():
                                   "sparq_packed_bytes", "sparq_requant", "sparq_strerror", "sparq_trim", "sparq_workspace_bytes"]
 
 
+def test_probe_library_exports_what_its_header_declares():
+    """The machine-ceiling micro-benchmarks (a library of their own): loads without a GPU, exports every declared call."""
+    text = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "sparq_probe.h")).read(), flags=re.S)
+    names = sorted(set(re.findall(r"\b(sparq_probe_[a-z0-9_]+)\s*\(", text)))
+    assert names == ["sparq_probe_copy", "sparq_probe_mfma_i8", "sparq_probe_mfma_i8_ops"]
+    path = os.path.join(ROOT, "paper_2105_11010_amd", "libsparq_probe.so")
+    if not os.path.exists(path):
+        import __graft_entry__
+        __graft_entry__.build()
+    L = ctypes.CDLL(path)
+    for n in names:
+        assert hasattr(L, n), n
+    L.sparq_probe_mfma_i8_ops.restype = ctypes.c_double
+    L.sparq_probe_mfma_i8_ops.argtypes = [ctypes.c_int32]
+    assert L.sparq_probe_mfma_i8_ops(1) == 2.0 * 32768 * 16 * 4 * 256
+    assert L.sparq_probe_mfma_i8(None, None, 1, None) == 1          # argument errors come back as codes, nothing is launched
+    assert L.sparq_probe_copy(None, None, 16, None) == 1
+
+
 def test_every_declared_symbol_is_exported(lib):
     for name in declared_symbols():
         assert hasattr(lib, name), name
