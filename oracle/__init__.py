@@ -70,6 +70,14 @@ def lib() -> ctypes.CDLL:
         L.sparq_requant_ref.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                         ctypes.c_int64, ctypes.c_int32]
         L.sparq_requant_ref.restype = ctypes.c_int
+        L.sparq_ref_packed_record_bytes.argtypes = [ctypes.POINTER(Mode), ctypes.c_int32]
+        L.sparq_ref_packed_record_bytes.restype = ctypes.c_int32
+        L.sparq_pack_act_ref.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32,
+                                         ctypes.POINTER(Mode), ctypes.c_int32]
+        L.sparq_pack_act_ref.restype = ctypes.c_int
+        L.sparq_unpack_act_ref.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32,
+                                           ctypes.POINTER(Mode), ctypes.c_int32]
+        L.sparq_unpack_act_ref.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -181,3 +189,38 @@ def conv_gemm_u8(x: np.ndarray, w: np.ndarray, factor: np.ndarray, stride=(1, 1)
     y = requant(acc, factor)
     return trim(y, **out_mode) if out_mode else y
 
+
+
+def packed_record_bytes(group: int = 1, **mode) -> int:
+    """Bytes of one 32-channel record of the packed form (Sections 3.1, 5.1, 6); 0 if the mode cannot be packed."""
+    m = _mode(**mode)
+    return int(lib().sparq_ref_packed_record_bytes(ctypes.byref(m), int(group)))
+
+
+def pack_act(x: np.ndarray, group: int = 1, **mode) -> np.ndarray:
+    """Packed records of the trimmed activations along the last axis of x: uint8 [rows, ceil(C/32) * record bytes]."""
+    x = np.ascontiguousarray(x, dtype=np.uint8)
+    C = x.shape[-1]
+    rows = x.size // C
+    rec = packed_record_bytes(group, **mode)
+    if rec == 0:
+        raise ValueError("this mode / group has no packed form")
+    packed = np.empty((rows, (C + 31) // 32 * rec), dtype=np.uint8)
+    m = _mode(**mode)
+    rc = lib().sparq_pack_act_ref(_ptr(x), _ptr(packed), rows, C, ctypes.byref(m), int(group))
+    if rc:
+        raise ValueError(f"sparq_pack_act_ref rejected its arguments (code {rc})")
+    return packed
+
+
+def unpack_act(packed: np.ndarray, shape, group: int = 1, **mode) -> np.ndarray:
+    """The uint8 tensor of `shape` the packed records encode."""
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    C = int(shape[-1])
+    rows = int(np.prod(shape)) // C
+    y = np.empty(shape, dtype=np.uint8)
+    m = _mode(**mode)
+    rc = lib().sparq_unpack_act_ref(_ptr(packed), _ptr(y), rows, C, ctypes.byref(m), int(group))
+    if rc:
+        raise ValueError(f"sparq_unpack_act_ref rejected its arguments (code {rc})")
+    return y

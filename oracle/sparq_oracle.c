@@ -259,3 +259,200 @@ int sparq_requant_ref(const int32_t *acc, const float *factor, uint8_t *y,
     return 0;
 }
 
+
+/* ------------------------------------------------------------------------ */
+/* packed storage of trimmed activations (Sections 3.1, 5.1, 6; Eq. 4)        */
+/* ------------------------------------------------------------------------ */
+
+static int popcount32(uint32_t v)
+{
+    int c = 0;
+    for (; v; v >>= 1)
+        c += (int)(v & 1u);
+    return c;
+}
+
+/* bits needed to number the placement options of S (5 options: 3 bits, 3 options: 2 bits, 2 options: 1 bit) */
+static int shift_ctrl_bits(uint32_t S)
+{
+    const int options = popcount32(S);
+    int bits = 0;
+    while ((1 << bits) < options)
+        ++bits;
+    return bits;
+}
+
+/* ShiftCtrl code of shift s: its rank among the allowed shifts, smallest first */
+static int shift_code(uint32_t S, int s)
+{
+    return popcount32(S & ((1u << s) - 1u));
+}
+
+static int shift_of_code(uint32_t S, int code)
+{
+    for (int t = 0; t < 8; ++t)
+        if ((S >> t) & 1u) {
+            if (code == 0)
+                return t;
+            --code;
+        }
+    return 0;
+}
+
+static void put_bits(uint8_t *area, int pos, int nbits, uint32_t value)
+{
+    for (int i = 0; i < nbits; ++i, ++pos)
+        if ((value >> i) & 1u)
+            area[pos >> 3] |= (uint8_t)(1u << (pos & 7));
+}
+
+static uint32_t get_bits(const uint8_t *area, int pos, int nbits)
+{
+    uint32_t v = 0;
+    for (int i = 0; i < nbits; ++i, ++pos)
+        v |= (uint32_t)((area[pos >> 3] >> (pos & 7)) & 1u) << i;
+    return v;
+}
+
+static int words_for_bits(int bits)
+{
+    return (bits + 31) / 32;
+}
+
+int32_t sparq_ref_packed_record_bytes(const sparq_ref_mode *mode, int32_t group)
+{
+    if (sparq_ref_mode_check(mode) || mode->window_bits == 8)
+        return 0;
+    if (group < 1 || group > 32 || 32 % group != 0 || (group > 1 && mode->pair))
+        return 0;
+    const int sb = shift_ctrl_bits(mode->shift_mask);
+    return 4 * (mode->window_bits + words_for_bits(32 / group * sb) + (mode->pair ? 1 : 0));
+}
+
+typedef struct {
+    int q, shift, owner;          /* n-bit datum, its shift-left, channel of the pair it is steered to (0 / 1) */
+} datum;
+
+/* The two data of a pair (a, b) as the multiplier of Eq. 4 takes them. */
+static void encode_pair(int a, int b, const sparq_ref_mode *mode, datum *d0, datum *d1)
+{
+    const int n = mode->window_bits;
+    const uint32_t S = mode->shift_mask;
+    const int R = mode->round_nearest;
+    int s;
+    if (mode->pair && (a == 0 || b == 0)) {
+        /* Eq. 2, cases in its order: second value zero -> the first keeps 2n bits; else first value zero -> the
+         * second does.  The kept value travels as a high and a low n-bit half steered to the same weight. */
+        const int owner = (b == 0) ? 0 : 1;
+        const int v = (b == 0) ? a : b;
+        const int tv = sparq_ref_trim_value(v, 2 * n, sparq_ref_wide_shift_mask(n, S), R, &s);
+        d0->q = (tv >> (s + n)) & ((1 << n) - 1);
+        d0->shift = s + n;
+        d1->q = (tv >> s) & ((1 << n) - 1);
+        d1->shift = s;
+        d0->owner = d1->owner = owner;
+        return;
+    }
+    const int ta = sparq_ref_trim_value(a, n, S, R, &s);
+    d0->q = ta >> s;
+    d0->shift = s;
+    d0->owner = 0;
+    const int tb = sparq_ref_trim_value(b, n, S, R, &s);
+    d1->q = tb >> s;
+    d1->shift = s;
+    d1->owner = 1;
+}
+
+int sparq_pack_act_ref(const uint8_t *x, uint8_t *packed, int64_t rows, int32_t C,
+                       const sparq_ref_mode *mode, int32_t group)
+{
+    const int32_t rec = sparq_ref_packed_record_bytes(mode, group);
+    if (!x || !packed || rows < 0 || C <= 0 || rec == 0)
+        return 1;
+    const int n = mode->window_bits;
+    const uint32_t S = mode->shift_mask;
+    const int sb = shift_ctrl_bits(S);
+    const int32_t nrec = (C + 31) / 32;
+    const int shift_words = words_for_bits(32 / group * sb);
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        const uint8_t *xr = x + r * C;
+        for (int32_t k = 0; k < nrec; ++k) {
+            uint8_t *data = packed + ((size_t)r * nrec + k) * rec;
+            uint8_t *shifts = data + 4 * n;
+            uint8_t *mux = shifts + 4 * shift_words;
+            memset(data, 0, (size_t)rec);
+            int v[32];
+            for (int i = 0; i < 32; ++i)
+                v[i] = (32 * k + i < C) ? xr[32 * k + i] : 0;     /* channels past C: zeros */
+            if (group > 1) {
+                /* Section 6: one ShiftCtrl for the whole group -- the placement bSPARQ picks for its largest value */
+                for (int g0 = 0; g0 < 32; g0 += group) {
+                    int top = 0, s;
+                    for (int i = g0; i < g0 + group; ++i)
+                        top = v[i] > top ? v[i] : top;
+                    sparq_ref_trim_value(top, n, S, 0, &s);
+                    put_bits(shifts, (g0 / group) * sb, sb, (uint32_t)shift_code(S, s));
+                    for (int i = g0; i < g0 + group; ++i) {
+                        int q = v[i] >> s;
+                        if (mode->round_nearest && s > 0) {
+                            q = (v[i] + (1 << (s - 1))) >> s;
+                            if (q > (1 << n) - 1)
+                                q = (1 << n) - 1;
+                        }
+                        put_bits(data, i * n, n, (uint32_t)q);
+                    }
+                }
+                continue;
+            }
+            for (int i = 0; i < 32; i += 2) {
+                datum d0, d1;
+                encode_pair(v[i], v[i + 1], mode, &d0, &d1);
+                put_bits(data, i * n, n, (uint32_t)d0.q);
+                put_bits(data, (i + 1) * n, n, (uint32_t)d1.q);
+                put_bits(shifts, i * sb, sb, (uint32_t)shift_code(S, d0.shift));
+                put_bits(shifts, (i + 1) * sb, sb, (uint32_t)shift_code(S, d1.shift));
+                if (mode->pair) {
+                    put_bits(mux, i, 1, (uint32_t)d0.owner);
+                    put_bits(mux, i + 1, 1, (uint32_t)d1.owner);
+                }
+            }
+        }
+    }
+    return 0;
+}
+
+int sparq_unpack_act_ref(const uint8_t *packed, uint8_t *y, int64_t rows, int32_t C,
+                         const sparq_ref_mode *mode, int32_t group)
+{
+    const int32_t rec = sparq_ref_packed_record_bytes(mode, group);
+    if (!packed || !y || rows < 0 || C <= 0 || rec == 0)
+        return 1;
+    const int n = mode->window_bits;
+    const uint32_t S = mode->shift_mask;
+    const int sb = shift_ctrl_bits(S);
+    const int32_t nrec = (C + 31) / 32;
+    const int shift_words = words_for_bits(32 / group * sb);
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        uint8_t *yr = y + r * C;
+        for (int32_t k = 0; k < nrec; ++k) {
+            const uint8_t *data = packed + ((size_t)r * nrec + k) * rec;
+            const uint8_t *shifts = data + 4 * n;
+            const uint8_t *mux = shifts + 4 * shift_words;
+            int out[32];
+            for (int i = 0; i < 32; ++i)
+                out[i] = 0;
+            for (int i = 0; i < 32; ++i) {
+                /* Eq. 4: every datum contributes 2^opt * x to the channel its MuxCtrl names */
+                const int q = (int)get_bits(data, i * n, n);
+                const int s = shift_of_code(S, (int)get_bits(shifts, (i / group) * sb, sb));
+                const int ch = mode->pair ? (i & ~1) + (int)get_bits(mux, i, 1) : i;
+                out[ch] += q << s;
+            }
+            for (int i = 0; i < 32 && 32 * k + i < C; ++i)
+                yr[32 * k + i] = (uint8_t)out[i];
+        }
+    }
+    return 0;
+}

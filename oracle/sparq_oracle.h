@@ -90,6 +90,39 @@ int sparq_dequant_ref(const int32_t *acc, const float *scale, double *out,
 int sparq_requant_ref(const int32_t *acc, const float *factor, uint8_t *y,
                       int64_t M, int32_t N);
 
+/* ---- packed storage of trimmed activations (Section 3.1: an n-bit window travels with an identifier of
+ * its position; Section 5.1: per 4-bit datum a ShiftCtrl field and, with vSPARQ, a 1-bit MuxCtrl; Section 6:
+ * ShiftCtrl may be shared by a number of activations) --------------------------------------------------------
+ *
+ * What is stored is what the multiplier of Eq. 4 consumes: per pair of channels two n-bit data, each with the
+ * shift that puts it back in place (ShiftCtrl = rank of that shift among the allowed ones) and, with vSPARQ, a
+ * MuxCtrl bit naming the channel of the pair whose weight it multiplies.  A pair with two non-zero values
+ * stores their two windows; a value whose partner is zero stores its 2n-bit window as a high and a low half
+ * (shifts t+n and t), both steered to that value's channel.  Decoding a channel is the sum of data << shift
+ * over the data steered to it.
+ *
+ * Layout (a reading: the paper fixes the fields, not their order in memory): a row of C channels is cut into
+ * records of 32 channels (the last one zero-filled); a record is three areas of whole little-endian 32-bit
+ * words: data (n words; datum k in bits [k*n, k*n+n) of the area), ShiftCtrl (field k in bits [k*sb, k*sb+sb),
+ * sb = bits needed to number the allowed shifts; with group = G > 1 one field per G consecutive channels),
+ * MuxCtrl (one word, bit k for datum k; absent when vSPARQ is off).  group > 1 is only defined with vSPARQ
+ * off: the group's shift is the one bSPARQ picks for its largest value, and every value of the group is
+ * trimmed (floor, or round half up saturating) at that shift -- a coarser quantiser than the per-value trim.
+ * This grouped form is a reading of a direction the paper leaves to future work: parity unpinned.
+ */
+
+/* Bytes of one 32-channel record; 0 if the mode cannot be packed (plain 8 bits, invalid, group not a divisor
+ * of 32, group > 1 with vSPARQ on). */
+int32_t sparq_ref_packed_record_bytes(const sparq_ref_mode *mode, int32_t group);
+
+/* packed receives rows * ceil(C/32) records holding T(x) (the trim is part of packing). */
+int sparq_pack_act_ref(const uint8_t *x, uint8_t *packed, int64_t rows, int32_t C,
+                       const sparq_ref_mode *mode, int32_t group);
+
+/* y[r][c] = the value the records encode. */
+int sparq_unpack_act_ref(const uint8_t *packed, uint8_t *y, int64_t rows, int32_t C,
+                         const sparq_ref_mode *mode, int32_t group);
+
 #ifdef __cplusplus
 }
 #endif
