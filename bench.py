@@ -301,6 +301,22 @@ def streaming_kernels(sq, S, torch, dev, dom, reps):
     ya = torch.empty_like(xa)
     ms = time_calls(torch, lambda i: sq.sparq_trim(xa, ya, dom["m"]), 2, reps)
     cold = {"GBps": round(2 * xa.numel() / ms / 1e6, 1), "bytes_per_launch": 2 * xa.numel(), "ms": round(ms, 4)}
+    # the packed storage codec (n-bit data + ShiftCtrl + MuxCtrl records) on the same cold tensor
+    codec = []
+    for label, mode, group in (("the workload's mode", dom["layer"].mode, 1), ("4b-3opt-floor-novS", S.Mode(4, S.OPT3, 0, 0), 1),
+                               ("4b-5opt-round-novS, ShiftCtrl shared by 8", S.Mode(4, S.OPT5, 1, 0), 8)):
+        if mode.window_bits == 8:
+            continue
+        pm = sq.mode(*mode.astuple())
+        nb = sq.sparq_packed_act_bytes(big.M, big.K, pm, group)
+        pk = torch.empty(nb, dtype=torch.uint8, device=dev)
+        ms_p = time_calls(torch, lambda i: sq.sparq_pack_act(xa, pk, pm, group), 2, reps)
+        ms_u = time_calls(torch, lambda i: sq.sparq_unpack_act(pk, ya, pm, group), 2, reps)
+        codec.append({"mode": mode.label if label.startswith("the") else label, "group": group,
+                      "bits_per_activation": round(8 * nb / xa.numel(), 3), "packed_bytes": nb,
+                      "pack_GBps": round((xa.numel() + nb) / ms_p / 1e6, 1), "unpack_GBps": round((xa.numel() + nb) / ms_u / 1e6, 1)})
+        del pk
+    out["packed_act"] = {"tensor": "config 3 A[65536][4608] uint8 (cold)", "GBps_counts": "bytes read + bytes written", "points": codec}
     del xa, ya
     out["trim"] = {"GBps": cold["GBps"], "frac_hbm_peak": round(cold["GBps"] / PEAK_HBM_GBPS, 4), "state": "cold (HBM)",
                    "tensor": "config 3 A[65536][4608] uint8", "bytes_per_launch": cold["bytes_per_launch"], "ms": cold["ms"],
@@ -487,6 +503,7 @@ def main():
         "roofline": roofline,
         "trim": stream["trim"],
         "dequant": stream["dequant"],
+        "packed_act": stream["packed_act"],
         "cpu_baseline": cpu,
     }
     if also:

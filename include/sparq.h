@@ -177,6 +177,55 @@ sparq_status sparq_conv_gemm_u8(const uint8_t *x, const void *packed_w,
 sparq_status sparq_requant(const int32_t *acc, const float *factor, uint8_t *y,
                            int64_t M, int32_t N, void *stream);
 
+/* ---- Packed storage of trimmed activations -------------------------------
+ * What SPARQ's multiplier consumes (Eq. 4) in place of 8-bit values: per pair
+ * of channels two n-bit data, each with a ShiftCtrl field (Section 3.1: the
+ * identifier of the window position; the rank of the shift among the allowed
+ * ones) and, with vSPARQ, a 1-bit MuxCtrl (Section 5.1) naming the channel of
+ * the pair whose weight it multiplies.  Two non-zero values store their two
+ * windows; a value whose partner is zero (second value zero first, as Eq. 2
+ * orders its cases) stores its 2n-bit window as a high half (shift t+n) and a
+ * low half (shift t), both steered to that value's channel.
+ * Layout: a row of C channels is cut into records of 32 channels (the last
+ * zero-filled); a record is, in little-endian 32-bit words: n data words
+ * (datum k in bits [k*n, k*n+n)), ceil(F*sb/32) ShiftCtrl words (field f in
+ * bits [f*sb, f*sb+sb), sb = bits to number the allowed shifts, F = 32/group),
+ * one MuxCtrl word (bit k: datum k goes to the odd channel; absent when
+ * mode->pair is 0).  Bits per activation: n + sb/group + pair, i.e. 4+3 for
+ * 5opt without vSPARQ, 4+2+1 for 3opt with it (the figures of Sections 3.1
+ * and 5.1), 8 for 5opt with vSPARQ.
+ * group = 1: per-value ShiftCtrl; unpacking gives exactly sparq_trim(x).
+ * group = 2, 4, 8, 16, 32 (mode->pair must be 0): ShiftCtrl shared by that
+ * many consecutive channels (Section 6) -- the placement bSPARQ picks for the
+ * group's largest value, every value of the group trimmed at it (floor, or
+ * round half up saturating): fewer bytes, a coarser quantiser.
+ * x, y: [rows][C] uint8; packed: 4-byte aligned, sparq_packed_act_bytes()
+ * bytes (0 = this mode / group has no packed form: plain 8 bits, invalid
+ * mode, bad group).  Too small a packed buffer returns SPARQ_EWORKSPACE. */
+size_t sparq_packed_act_bytes(int64_t rows, int32_t C, const sparq_mode *mode, int32_t group);
+
+/* packed = the records of T(x): the trim is part of packing. */
+sparq_status sparq_pack_act(const uint8_t *x, void *packed, size_t packed_bytes,
+                            int64_t rows, int32_t C, const sparq_mode *mode,
+                            int32_t group, void *stream);
+
+/* y = the 8-bit values the records encode. */
+sparq_status sparq_unpack_act(const void *packed, size_t packed_bytes, uint8_t *y,
+                              int64_t rows, int32_t C, const sparq_mode *mode,
+                              int32_t group, void *stream);
+
+/* sparq_conv_gemm on an input stored in packed form (as written by
+ * sparq_pack_act with the same mode and group over rows = B*H*W pixels of C
+ * channels): Eq. 1 over the values the records encode.  The records are
+ * expanded into the workspace and contracted at plain 8 bits, so workspace
+ * must hold sparq_conv_packed_workspace_bytes() bytes (256-byte aligned). */
+size_t sparq_conv_packed_workspace_bytes(const sparq_conv_desc *desc, const sparq_mode *mode);
+sparq_status sparq_conv_gemm_packed(const void *packed_x, size_t packed_x_bytes, int32_t group,
+                                    const void *packed_w, const sparq_conv_desc *desc,
+                                    const sparq_mode *mode, int32_t *acc, const float *scale,
+                                    float *out, void *workspace, size_t workspace_bytes,
+                                    void *stream);
+
 /* Static description of a status code. */
 const char *sparq_strerror(sparq_status status);
 

@@ -62,6 +62,16 @@ def _load() -> ctypes.CDLL:
     L.sparq_conv_gemm_u8.restype = ctypes.c_int
     L.sparq_requant.argtypes = [vp, vp, vp, i64, i32, vp]
     L.sparq_requant.restype = ctypes.c_int
+    L.sparq_packed_act_bytes.argtypes = [i64, i32, pm, i32]
+    L.sparq_packed_act_bytes.restype = sz
+    L.sparq_pack_act.argtypes = [vp, vp, sz, i64, i32, pm, i32, vp]
+    L.sparq_pack_act.restype = ctypes.c_int
+    L.sparq_unpack_act.argtypes = [vp, sz, vp, i64, i32, pm, i32, vp]
+    L.sparq_unpack_act.restype = ctypes.c_int
+    L.sparq_conv_packed_workspace_bytes.argtypes = [pd, pm]
+    L.sparq_conv_packed_workspace_bytes.restype = sz
+    L.sparq_conv_gemm_packed.argtypes = [vp, sz, i32, vp, pd, pm, vp, vp, vp, vp, sz, vp]
+    L.sparq_conv_gemm_packed.restype = ctypes.c_int
     L.sparq_strerror.argtypes = [ctypes.c_int]
     L.sparq_strerror.restype = ctypes.c_char_p
     return L
@@ -207,3 +217,44 @@ def sparq_requant(acc: torch.Tensor, factor: torch.Tensor, y: torch.Tensor) -> N
         raise ValueError("shape mismatch")
     _check(lib.sparq_requant(_dev(acc, torch.int32, "acc"), _dev(factor, torch.float32, "factor"),
                              _dev(y, torch.uint8, "y"), M, N, _stream()), "sparq_requant")
+
+
+def sparq_packed_act_bytes(rows: int, C: int, m: SparqMode, group: int = 1) -> int:
+    """Bytes of the packed form of [rows][C] activations (0: this mode / group has none)."""
+    return int(lib.sparq_packed_act_bytes(int(rows), int(C), ctypes.byref(m), int(group)))
+
+
+def sparq_pack_act(x: torch.Tensor, packed: torch.Tensor, m: SparqMode, group: int = 1) -> None:
+    """packed (uint8 device buffer) = the n-bit data + ShiftCtrl + MuxCtrl records of the trimmed x (last axis = channels)."""
+    C = x.shape[-1]
+    _check(lib.sparq_pack_act(_dev(x, torch.uint8, "x"), _dev(packed, torch.uint8, "packed"), packed.numel(),
+                              x.numel() // C, C, ctypes.byref(m), int(group), _stream()), "sparq_pack_act")
+
+
+def sparq_unpack_act(packed: torch.Tensor, y: torch.Tensor, m: SparqMode, group: int = 1) -> None:
+    """y (uint8, last axis = channels) = the values the records encode."""
+    C = y.shape[-1]
+    _check(lib.sparq_unpack_act(_dev(packed, torch.uint8, "packed"), packed.numel(), _dev(y, torch.uint8, "y"),
+                                y.numel() // C, C, ctypes.byref(m), int(group), _stream()), "sparq_unpack_act")
+
+
+def sparq_conv_packed_workspace_bytes(d: SparqConvDesc, m: SparqMode) -> int:
+    return int(lib.sparq_conv_packed_workspace_bytes(ctypes.byref(d), ctypes.byref(m)))
+
+
+def sparq_conv_gemm_packed(packed_x: torch.Tensor, group: int, packed_w: torch.Tensor, d: SparqConvDesc, m: SparqMode,
+                           acc: Optional[torch.Tensor] = None, scale: Optional[torch.Tensor] = None,
+                           out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> None:
+    """sparq_conv_gemm on an input held in packed storage (written by sparq_pack_act with the same mode and group)."""
+    M = out_rows(d)
+    for t, nm in ((acc, "acc"), (out, "out")):
+        if t is not None and t.numel() != M * d.N:
+            raise ValueError(f"{nm} must hold M*N = {M * d.N} elements")
+    if scale is not None and scale.numel() != d.N:
+        raise ValueError("scale must hold N elements")
+    ws_ptr = _dev(workspace, torch.uint8, "workspace")
+    ws_bytes = workspace.numel() if workspace is not None else 0
+    _check(lib.sparq_conv_gemm_packed(_dev(packed_x, torch.uint8, "packed_x"), packed_x.numel(), int(group),
+                                      _dev(packed_w, torch.uint8, "packed_w"), ctypes.byref(d), ctypes.byref(m),
+                                      _dev(acc, torch.int32, "acc"), _dev(scale, torch.float32, "scale"),
+                                      _dev(out, torch.float32, "out"), ws_ptr, ws_bytes, _stream()), "sparq_conv_gemm_packed")

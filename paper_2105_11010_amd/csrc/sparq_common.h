@@ -221,6 +221,10 @@ sparq_status launch_trim_pad(const uint8_t* x, uint8_t* xp, int64_t pixels, int 
                              const sparq_mode* mode, hipStream_t stream);
 
 
+// Implemented in sparq_packed_act.hip: the 8-bit values a packed activation tensor encodes.
+sparq_status launch_unpack_act(const void* packed, uint8_t* y, int64_t rows, int C, const sparq_mode* mode, int group,
+                               hipStream_t stream);
+
 // Implemented in sparq_elementwise.hip: kernel-based clear of a 16-byte aligned buffer.
 sparq_status launch_zero(void* dst, size_t bytes, hipStream_t stream);
 

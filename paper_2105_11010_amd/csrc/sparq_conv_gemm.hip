@@ -466,6 +466,37 @@ extern "C" sparq_status sparq_conv_gemm_static_ws(const uint8_t* x, const void* 
     return conv_launch(x, packed_w, desc, mode, acc, scale, out, nullptr, nullptr, ws, need, stream);
 }
 
+// ---- input in packed storage (Sections 3.1, 5.1, 6): records expanded into the workspace, contracted at 8 bits ----
+namespace {
+const sparq_mode kPlainMode = {8, 1, 0, 0};
+}
+
+extern "C" size_t sparq_conv_packed_workspace_bytes(const sparq_conv_desc* desc, const sparq_mode* mode) {
+    ConvGeom g;
+    if (!conv_geom(desc, &g) || !mode_valid(mode)) return 0;
+    return (size_t)round_up((int64_t)g.x_bytes, 256) + sparq_workspace_bytes(desc, &kPlainMode);
+}
+
+extern "C" sparq_status sparq_conv_gemm_packed(const void* packed_x, size_t packed_x_bytes, int32_t group,
+                                               const void* packed_w, const sparq_conv_desc* desc, const sparq_mode* mode,
+                                               int32_t* acc, const float* scale, float* out, void* workspace,
+                                               size_t workspace_bytes, void* stream) {
+    ConvGeom g;
+    if (!packed_x || !conv_geom(desc, &g) || !mode_valid(mode) || (!acc && !out)) return SPARQ_EINVAL;
+    const int64_t pixels = (int64_t)g.B * g.H * g.W;
+    const size_t need_packed = sparq_packed_act_bytes(pixels, g.C, mode, group);
+    if (need_packed == 0 || !aligned(packed_x, 4)) return SPARQ_EINVAL;
+    if (packed_x_bytes < need_packed) return SPARQ_EWORKSPACE;
+    if (!workspace || !aligned(workspace, 256)) return SPARQ_EINVAL;
+    if (workspace_bytes < sparq_conv_packed_workspace_bytes(desc, mode)) return SPARQ_EWORKSPACE;
+    uint8_t* xu = static_cast<uint8_t*>(workspace);
+    const size_t x_room = (size_t)round_up((int64_t)g.x_bytes, 256);
+    const sparq_status st = launch_unpack_act(packed_x, xu, pixels, g.C, mode, group, static_cast<hipStream_t>(stream));
+    if (st != SPARQ_OK) return st;
+    return conv_launch(xu, packed_w, desc, &kPlainMode, acc, scale, out, nullptr, nullptr, xu + x_room,
+                       workspace_bytes - x_room, stream);
+}
+
 extern "C" sparq_status sparq_conv_gemm_u8(const uint8_t* x, const void* packed_w, const sparq_conv_desc* desc,
                                            const sparq_mode* mode, const float* factor, uint8_t* y,
                                            const sparq_mode* out_mode, void* workspace, size_t workspace_bytes,
