@@ -70,6 +70,10 @@ def lib() -> ctypes.CDLL:
         L.sparq_requant_ref.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                         ctypes.c_int64, ctypes.c_int32]
         L.sparq_requant_ref.restype = ctypes.c_int
+        L.sparq_conv_gemm_sparse24_ref.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.POINTER(Conv),
+                                                   ctypes.POINTER(Mode), ctypes.c_void_p, ctypes.c_int64,
+                                                   ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        L.sparq_conv_gemm_sparse24_ref.restype = ctypes.c_int
         L.sparq_ref_packed_record_bytes.argtypes = [ctypes.POINTER(Mode), ctypes.c_int32]
         L.sparq_ref_packed_record_bytes.restype = ctypes.c_int32
         L.sparq_pack_act_ref.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32,
@@ -224,3 +228,33 @@ def unpack_act(packed: np.ndarray, shape, group: int = 1, **mode) -> np.ndarray:
     if rc:
         raise ValueError(f"sparq_unpack_act_ref rejected its arguments (code {rc})")
     return y
+
+
+def conv_gemm_sparse24(x: np.ndarray, w_vals: np.ndarray, w_idx: np.ndarray, stride=(1, 1), pad=(0, 0), *, scale=None,
+                       rows=None, **mode):
+    """Convolution with 2:4 pruned weights (Section 4, sparse tensor core): w_vals int8 / w_idx uint8 [N,KH,KW,C/2];
+    the two activations an output channel's coordinates pick from a group of four form its vSPARQ pair.
+    Returns (acc int32, out float64 or None) like conv_gemm."""
+    x = np.ascontiguousarray(x, dtype=np.uint8)
+    w_vals = np.ascontiguousarray(w_vals, dtype=np.int8)
+    w_idx = np.ascontiguousarray(w_idx, dtype=np.uint8)
+    B, H, W, C = x.shape
+    N, KH, KW, C2 = w_vals.shape
+    assert 2 * C2 == C and w_idx.shape == w_vals.shape
+    d = Conv(B, H, W, C, N, KH, KW, stride[0], stride[1], pad[0], pad[1])
+    Ho, Wo = conv_out_hw(H, W, KH, KW, stride, pad)
+    ridx, nr = None, B * Ho * Wo
+    if rows is not None:
+        ridx = np.ascontiguousarray(rows, dtype=np.int64)
+        nr = ridx.size
+    acc = np.empty((nr, N), dtype=np.int32)
+    out = sc = None
+    if scale is not None:
+        sc = np.ascontiguousarray(scale, dtype=np.float32)
+        out = np.empty((nr, N), dtype=np.float64)
+    m = _mode(**mode)
+    rc = lib().sparq_conv_gemm_sparse24_ref(_ptr(x), _ptr(w_vals), _ptr(w_idx), ctypes.byref(d), ctypes.byref(m),
+                                            _ptr(ridx), nr, _ptr(acc), _ptr(sc), _ptr(out))
+    if rc:
+        raise ValueError(f"sparq_conv_gemm_sparse24_ref failed (code {rc})")
+    return acc, out

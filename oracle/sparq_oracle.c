@@ -213,6 +213,82 @@ int sparq_conv_gemm_ref(const uint8_t *x, const int8_t *w,
 }
 
 /* ------------------------------------------------------------------------ */
+/* 2:4 weight sparsity: activations picked by the weights' coordinates, then */
+/* paired (Section 4, sparse tensor core; Section 5.3)                        */
+/* ------------------------------------------------------------------------ */
+
+int sparq_conv_gemm_sparse24_ref(const uint8_t *x, const int8_t *w_vals, const uint8_t *w_idx,
+                                 const sparq_ref_conv *d, const sparq_ref_mode *mode,
+                                 const int64_t *row_idx, int64_t n_rows,
+                                 int32_t *acc, const float *scale, double *out)
+{
+    if (!x || !w_vals || !w_idx || !d || sparq_ref_mode_check(mode))
+        return 1;
+    if (d->B <= 0 || d->H <= 0 || d->W <= 0 || d->C <= 0 || d->C % 4 != 0 || d->N <= 0 ||
+        d->KH <= 0 || d->KW <= 0 || d->stride_h <= 0 || d->stride_w <= 0 ||
+        d->pad_h < 0 || d->pad_w < 0)
+        return 1;
+    if (d->H + 2 * d->pad_h < d->KH || d->W + 2 * d->pad_w < d->KW)
+        return 1;
+    if (out && !scale)
+        return 1;
+    const int64_t half = (int64_t)d->N * d->KH * d->KW * (d->C / 2);
+    for (int64_t i = 0; i < half; i += 2)
+        if (w_idx[i] > 3 || w_idx[i + 1] > 3 || w_idx[i] >= w_idx[i + 1])
+            return 1;                        /* two distinct positions inside the group, smaller first */
+    const int64_t Ho = (d->H + 2 * d->pad_h - d->KH) / d->stride_h + 1;
+    const int64_t Wo = (d->W + 2 * d->pad_w - d->KW) / d->stride_w + 1;
+    const int64_t M = (int64_t)d->B * Ho * Wo;
+    const int64_t rows = row_idx ? n_rows : M;
+    if (row_idx)
+        for (int64_t i = 0; i < rows; ++i)
+            if (row_idx[i] < 0 || row_idx[i] >= M)
+                return 1;
+    const int groups = d->C / 4;
+    const sparq_ref_mode pair_mode = *mode;
+    int overflow = 0;
+#pragma omp parallel for schedule(static) reduction(| : overflow)
+    for (int64_t i = 0; i < rows; ++i) {
+        const int64_t m = row_idx ? row_idx[i] : i;
+        const int64_t ox = m % Wo;
+        const int64_t oy = (m / Wo) % Ho;
+        const int64_t b = m / (Wo * Ho);
+        for (int32_t n = 0; n < d->N; ++n) {
+            int64_t sum = 0;
+            for (int32_t kh = 0; kh < d->KH; ++kh) {
+                const int64_t iy = oy * d->stride_h - d->pad_h + kh;
+                if (iy < 0 || iy >= d->H)
+                    continue;                /* outside the image every picked activation is zero */
+                for (int32_t kw = 0; kw < d->KW; ++kw) {
+                    const int64_t ix = ox * d->stride_w - d->pad_w + kw;
+                    if (ix < 0 || ix >= d->W)
+                        continue;
+                    const uint8_t *xp = x + ((b * d->H + iy) * d->W + ix) * d->C;
+                    const int64_t wbase = (((int64_t)n * d->KH + kh) * d->KW + kw) * (d->C / 2);
+                    for (int g = 0; g < groups; ++g) {
+                        /* the multiplexers of the sparse tensor core: the coordinates pick two of the four */
+                        const uint8_t picked[2] = { xp[4 * g + w_idx[wbase + 2 * g]],
+                                                    xp[4 * g + w_idx[wbase + 2 * g + 1]] };
+                        uint8_t trimmed[2];
+                        /* ... and the two picked values are one vSPARQ pair (a vector of two channels) */
+                        trim_vector(picked, trimmed, 2, &pair_mode);
+                        sum += (int64_t)trimmed[0] * w_vals[wbase + 2 * g] +
+                               (int64_t)trimmed[1] * w_vals[wbase + 2 * g + 1];
+                    }
+                }
+            }
+            if (sum > INT32_MAX || sum < INT32_MIN)
+                overflow = 1;
+            if (acc)
+                acc[i * d->N + n] = (int32_t)sum;
+            if (out)
+                out[i * d->N + n] = (double)sum * (double)scale[n];
+        }
+    }
+    return overflow ? 2 : 0;
+}
+
+/* ------------------------------------------------------------------------ */
 /* dequantisation (Section 5: per-layer activation scale times per-kernel    */
 /* weight scale, folded into one factor per output channel)                  */
 /* ------------------------------------------------------------------------ */

@@ -90,6 +90,22 @@ int sparq_dequant_ref(const int32_t *acc, const float *scale, double *out,
 int sparq_requant_ref(const int32_t *acc, const float *factor, uint8_t *y,
                       int64_t M, int32_t N);
 
+/* ---- 2:4 structured weight sparsity (Section 4, sparse tensor core; Section 5.3) ----------------------------
+ * Of every four adjacent weights along the input channels two are kept, stored with their coordinates:
+ * w_vals [N][KH][KW][C/2] int8 and w_idx [N][KH][KW][C/2], entries 2g and 2g+1 of a tap holding the positions
+ * (0..3, ascending, distinct) of the kept weights of group g (channels 4g .. 4g+3).  "The stored coordinates
+ * indicate which activations are picked"; "then vSPARQ comes into play, inspecting pairs of activations": the
+ * two activations an output channel picks from a group form its vSPARQ pair (a reading: the figure that shows
+ * the pairing is not available), so the trim of an activation depends on the output channel's coordinates.
+ *   acc[m][n] = sum over taps, groups g of  ta * w_vals[..2g] + tb * w_vals[..2g+1],
+ *   (ta, tb) = the pair rule of Eq. 2 on (x[..4g + idx0], x[..4g + idx1])   (each trimmed alone if vSPARQ is off).
+ * C must be a multiple of 4.  Returns 1 on bad arguments (also on bad coordinates), 2 on int32 overflow.
+ * Parity unpinned against the authors' simulation on the choice of pairs; everything else follows Eq. 1-2. */
+int sparq_conv_gemm_sparse24_ref(const uint8_t *x, const int8_t *w_vals, const uint8_t *w_idx,
+                                 const sparq_ref_conv *desc, const sparq_ref_mode *mode,
+                                 const int64_t *row_idx, int64_t n_rows,
+                                 int32_t *acc, const float *scale, double *out);
+
 /* ---- packed storage of trimmed activations (Section 3.1: an n-bit window travels with an identifier of
  * its position; Section 5.1: per 4-bit datum a ShiftCtrl field and, with vSPARQ, a 1-bit MuxCtrl; Section 6:
  * ShiftCtrl may be shared by a number of activations) --------------------------------------------------------

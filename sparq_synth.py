@@ -140,6 +140,32 @@ def gen_requant(layer: "ConvLayer", rng: np.random.Generator) -> np.ndarray:
     return (rng.uniform(0.7, 1.3, size=layer.N) * (0.044 / np.sqrt(layer.K))).astype(np.float32)
 
 
+def gen_sparse24_weights(shape, rng: np.random.Generator, natural_pairs: bool = False):
+    """2:4 structured-sparse int8 weights for a dense shape [N,KH,KW,C] (C a multiple of 4), in compressed form:
+    (values int8 [N,KH,KW,C/2], coordinates uint8 [N,KH,KW,C/2]); of every four adjacent input channels two random
+    positions are kept (ascending).  About 3 % of the kept values are zero, as a pruned-and-quantised layer has.
+    natural_pairs: only the position pairs (0,1) and (2,3) are drawn."""
+    N, KH, KW, C = shape
+    assert C % 4 == 0
+    groups = N * KH * KW * (C // 4)
+    table = np.array([[0, 1], [2, 3]] if natural_pairs else [[0, 1], [0, 2], [0, 3], [1, 2], [1, 3], [2, 3]], dtype=np.uint8)
+    idx = table[rng.integers(0, len(table), size=groups)]
+    vals = rng.integers(-127, 128, size=(groups, 2), dtype=np.int64).astype(np.int8)
+    vals[rng.random((groups, 2)) < 0.03] = 0
+    return vals.reshape(N, KH, KW, C // 2), idx.reshape(N, KH, KW, C // 2)
+
+
+def sparse24_to_dense(w_vals: np.ndarray, w_idx: np.ndarray) -> np.ndarray:
+    """The dense [N,KH,KW,C] weights a compressed 2:4 tensor stands for (zeros at the pruned positions)."""
+    N, KH, KW, C2 = w_vals.shape
+    dense = np.zeros((N * KH * KW * (C2 // 2), 4), dtype=np.int8)
+    v, i = w_vals.reshape(-1, 2), w_idx.reshape(-1, 2).astype(np.int64)
+    r = np.arange(len(v))
+    dense[r, i[:, 0]] = v[:, 0]
+    dense[r, i[:, 1]] = v[:, 1]
+    return dense.reshape(N, KH, KW, 2 * C2)
+
+
 def gen_layer(config: int, layer: ConvLayer):
     """(x uint8 NHWC, w int8 [N,KH,KW,C], scale fp32 [N]) for one layer."""
     rng = rng_for(config, layer.index)
