@@ -226,6 +226,35 @@ sparq_status sparq_conv_gemm_packed(const void *packed_x, size_t packed_x_bytes,
                                     float *out, void *workspace, size_t workspace_bytes,
                                     void *stream);
 
+/* ---- 2:4 pruned weights (Section 4, sparse tensor core; Section 5.3) --------
+ * Of every four adjacent weights along the input channels two are kept and
+ * stored with their coordinates: w_vals int8 [N][KH][KW][C/2] and w_idx uint8
+ * [N][KH][KW][C/2], entries 2g and 2g+1 of a tap being the positions (0..3,
+ * ascending, distinct -- a precondition, not checked on the device) of the
+ * kept weights of group g (channels 4g..4g+3); C must be a multiple of 4.
+ * The coordinates pick two of the four activations, and the picked two are
+ * that output channel's vSPARQ pair:
+ *   acc[m][n] = sum over taps and groups of ta * w_vals[..2g] + tb * w_vals[..2g+1],
+ *   (ta, tb) = the pair rule of Eq. 2 on the two picked activations (each
+ *   trimmed on its own when mode->pair is 0).
+ * MI355X has no datapath that trims after a sparse selection; the result is
+ * computed exactly on the dense int8 matrix cores over an expanded problem
+ * (four dense multiply-accumulates per kept weight when vSPARQ is on; the
+ * decompressed weights on the ordinary path when it is off).
+ * packed: 256-byte aligned, sparq_sparse24_packed_bytes() bytes, filled once
+ * by sparq_pack_weights_sparse24 for the same desc and mode; workspace:
+ * 256-byte aligned, sparq_sparse24_workspace_bytes() bytes.  Everything else
+ * as for sparq_conv_gemm (x 16-byte aligned, acc / out / scale). */
+size_t sparq_sparse24_packed_bytes(const sparq_conv_desc *desc, const sparq_mode *mode);
+sparq_status sparq_pack_weights_sparse24(const int8_t *w_vals, const uint8_t *w_idx,
+                                         const sparq_conv_desc *desc, const sparq_mode *mode,
+                                         void *packed, size_t packed_bytes, void *stream);
+size_t sparq_sparse24_workspace_bytes(const sparq_conv_desc *desc, const sparq_mode *mode);
+sparq_status sparq_conv_gemm_sparse24(const uint8_t *x, const void *packed,
+                                      const sparq_conv_desc *desc, const sparq_mode *mode,
+                                      int32_t *acc, const float *scale, float *out,
+                                      void *workspace, size_t workspace_bytes, void *stream);
+
 /* Static description of a status code. */
 const char *sparq_strerror(sparq_status status);
 

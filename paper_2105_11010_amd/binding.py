@@ -72,6 +72,14 @@ def _load() -> ctypes.CDLL:
     L.sparq_conv_packed_workspace_bytes.restype = sz
     L.sparq_conv_gemm_packed.argtypes = [vp, sz, i32, vp, pd, pm, vp, vp, vp, vp, sz, vp]
     L.sparq_conv_gemm_packed.restype = ctypes.c_int
+    L.sparq_sparse24_packed_bytes.argtypes = [pd, pm]
+    L.sparq_sparse24_packed_bytes.restype = sz
+    L.sparq_pack_weights_sparse24.argtypes = [vp, vp, pd, pm, vp, sz, vp]
+    L.sparq_pack_weights_sparse24.restype = ctypes.c_int
+    L.sparq_sparse24_workspace_bytes.argtypes = [pd, pm]
+    L.sparq_sparse24_workspace_bytes.restype = sz
+    L.sparq_conv_gemm_sparse24.argtypes = [vp, vp, pd, pm, vp, vp, vp, vp, sz, vp]
+    L.sparq_conv_gemm_sparse24.restype = ctypes.c_int
     L.sparq_strerror.argtypes = [ctypes.c_int]
     L.sparq_strerror.restype = ctypes.c_char_p
     return L
@@ -258,3 +266,38 @@ def sparq_conv_gemm_packed(packed_x: torch.Tensor, group: int, packed_w: torch.T
                                       _dev(packed_w, torch.uint8, "packed_w"), ctypes.byref(d), ctypes.byref(m),
                                       _dev(acc, torch.int32, "acc"), _dev(scale, torch.float32, "scale"),
                                       _dev(out, torch.float32, "out"), ws_ptr, ws_bytes, _stream()), "sparq_conv_gemm_packed")
+
+
+def sparq_sparse24_packed_bytes(d: SparqConvDesc, m: SparqMode) -> int:
+    return int(lib.sparq_sparse24_packed_bytes(ctypes.byref(d), ctypes.byref(m)))
+
+
+def sparq_sparse24_workspace_bytes(d: SparqConvDesc, m: SparqMode) -> int:
+    return int(lib.sparq_sparse24_workspace_bytes(ctypes.byref(d), ctypes.byref(m)))
+
+
+def sparq_pack_weights_sparse24(w_vals: torch.Tensor, w_idx: torch.Tensor, d: SparqConvDesc, m: SparqMode,
+                                packed: torch.Tensor) -> None:
+    """2:4 compressed weights (values int8 and coordinates uint8, both [N,KH,KW,C/2]) -> packed device buffer."""
+    if tuple(w_vals.shape) != (d.N, d.KH, d.KW, d.C // 2) or w_idx.shape != w_vals.shape:
+        raise ValueError("weight shapes do not match the descriptor")
+    _check(lib.sparq_pack_weights_sparse24(_dev(w_vals, torch.int8, "w_vals"), _dev(w_idx, torch.uint8, "w_idx"),
+                                           ctypes.byref(d), ctypes.byref(m), _dev(packed, torch.uint8, "packed"),
+                                           packed.numel(), _stream()), "sparq_pack_weights_sparse24")
+
+
+def sparq_conv_gemm_sparse24(x: torch.Tensor, packed: torch.Tensor, d: SparqConvDesc, m: SparqMode,
+                             acc: Optional[torch.Tensor] = None, scale: Optional[torch.Tensor] = None,
+                             out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> None:
+    """The convolution with 2:4 pruned weights: activations picked by the weights' coordinates, then paired."""
+    if x.numel() != d.B * d.H * d.W * d.C:
+        raise ValueError("activation size does not match the descriptor")
+    M = out_rows(d)
+    for t, nm in ((acc, "acc"), (out, "out")):
+        if t is not None and t.numel() != M * d.N:
+            raise ValueError(f"{nm} must hold M*N = {M * d.N} elements")
+    ws_ptr = _dev(workspace, torch.uint8, "workspace")
+    ws_bytes = workspace.numel() if workspace is not None else 0
+    _check(lib.sparq_conv_gemm_sparse24(_dev(x, torch.uint8, "x"), _dev(packed, torch.uint8, "packed"), ctypes.byref(d),
+                                        ctypes.byref(m), _dev(acc, torch.int32, "acc"), _dev(scale, torch.float32, "scale"),
+                                        _dev(out, torch.float32, "out"), ws_ptr, ws_bytes, _stream()), "sparq_conv_gemm_sparse24")

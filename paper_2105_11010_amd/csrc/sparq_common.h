@@ -221,6 +221,13 @@ sparq_status launch_trim_pad(const uint8_t* x, uint8_t* xp, int64_t pixels, int 
                              const sparq_mode* mode, hipStream_t stream);
 
 
+// Implemented in sparq_sparse24.hip: the expanded activation tensor (16 bytes per group of four channels) and the
+// dense (expand: 16 bytes per group, else 4) form of 2:4 compressed weights.
+sparq_status launch_sparse24_expand_act(const uint8_t* x, uint8_t* xe, int64_t pixels, int C, const sparq_mode* mode,
+                                        hipStream_t stream);
+sparq_status launch_sparse24_expand_weights(const int8_t* vals, const uint8_t* idx, int8_t* dense, int64_t groups, bool expand,
+                                            hipStream_t stream);
+
 // Implemented in sparq_packed_act.hip: the 8-bit values a packed activation tensor encodes.
 sparq_status launch_unpack_act(const void* packed, uint8_t* y, int64_t rows, int C, const sparq_mode* mode, int group,
                                hipStream_t stream);

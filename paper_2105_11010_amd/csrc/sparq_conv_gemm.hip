@@ -497,6 +497,72 @@ extern "C" sparq_status sparq_conv_gemm_packed(const void* packed_x, size_t pack
                        workspace_bytes - x_room, stream);
 }
 
+// ---- 2:4 pruned weights (Section 4, sparse tensor core; Section 5.3): see sparq_sparse24.hip ----
+namespace {
+// The dense problem that is actually contracted: with vSPARQ on, 16 expanded channels per group of four.
+bool sparse24_geometry(const sparq_conv_desc* desc, const sparq_mode* mode, sparq_conv_desc* eff, bool* expand) {
+    ConvGeom g;
+    if (!desc || desc->C % 4 != 0 || !conv_geom(desc, &g) || !mode_valid(mode)) return false;
+    *expand = mode->pair && mode->window_bits != 8;
+    *eff = *desc;
+    if (*expand) {
+        if ((int64_t)desc->C * 4 > 0x7FFFFFFF) return false;
+        eff->C = desc->C * 4;
+    }
+    return conv_geom(eff, &g);
+}
+const sparq_mode kNoPairPlain = {8, 1, 0, 0};
+}  // namespace
+
+extern "C" size_t sparq_sparse24_packed_bytes(const sparq_conv_desc* desc, const sparq_mode* mode) {
+    sparq_conv_desc eff;
+    bool expand;
+    if (!sparse24_geometry(desc, mode, &eff, &expand)) return 0;
+    const size_t dense = (size_t)round_up((int64_t)eff.N * eff.KH * eff.KW * eff.C, 256);
+    return (size_t)round_up((int64_t)sparq_packed_bytes(&eff), 256) + dense;      // packed tiles + room to decompress into
+}
+
+extern "C" sparq_status sparq_pack_weights_sparse24(const int8_t* w_vals, const uint8_t* w_idx, const sparq_conv_desc* desc,
+                                                    const sparq_mode* mode, void* packed, size_t packed_bytes, void* stream) {
+    sparq_conv_desc eff;
+    bool expand;
+    if (!w_vals || !w_idx || !packed || !sparse24_geometry(desc, mode, &eff, &expand) || !aligned(packed, 256)) return SPARQ_EINVAL;
+    if (packed_bytes < sparq_sparse24_packed_bytes(desc, mode)) return SPARQ_EWORKSPACE;
+    const size_t tiles = (size_t)round_up((int64_t)sparq_packed_bytes(&eff), 256);
+    int8_t* dense = static_cast<int8_t*>(packed) + tiles;
+    const int64_t groups = (int64_t)desc->N * desc->KH * desc->KW * (desc->C / 4);
+    const sparq_status st = launch_sparse24_expand_weights(w_vals, w_idx, dense, groups, expand, static_cast<hipStream_t>(stream));
+    if (st != SPARQ_OK) return st;
+    return sparq_pack_weights(dense, &eff, packed, tiles, stream);
+}
+
+extern "C" size_t sparq_sparse24_workspace_bytes(const sparq_conv_desc* desc, const sparq_mode* mode) {
+    sparq_conv_desc eff;
+    bool expand;
+    if (!sparse24_geometry(desc, mode, &eff, &expand)) return 0;
+    if (!expand) return sparq_workspace_bytes(desc, mode);
+    return (size_t)round_up((int64_t)eff.B * eff.H * eff.W * eff.C, 256) + sparq_workspace_bytes(&eff, &kNoPairPlain);
+}
+
+extern "C" sparq_status sparq_conv_gemm_sparse24(const uint8_t* x, const void* packed, const sparq_conv_desc* desc,
+                                                 const sparq_mode* mode, int32_t* acc, const float* scale, float* out,
+                                                 void* workspace, size_t workspace_bytes, void* stream) {
+    sparq_conv_desc eff;
+    bool expand;
+    if (!x || !packed || (!acc && !out) || !sparse24_geometry(desc, mode, &eff, &expand)) return SPARQ_EINVAL;
+    if (!expand)      // nothing depends on the partner: the decompressed weights, the ordinary path
+        return conv_launch(x, packed, desc, mode, acc, scale, out, nullptr, nullptr, workspace, workspace_bytes, stream);
+    if (!aligned(x, 4) || !workspace || !aligned(workspace, 256)) return SPARQ_EINVAL;
+    if (workspace_bytes < sparq_sparse24_workspace_bytes(desc, mode)) return SPARQ_EWORKSPACE;
+    const int64_t pixels = (int64_t)desc->B * desc->H * desc->W;
+    const size_t x_room = (size_t)round_up(pixels * eff.C, 256);
+    uint8_t* xe = static_cast<uint8_t*>(workspace);
+    const sparq_status st = launch_sparse24_expand_act(x, xe, pixels, desc->C, mode, static_cast<hipStream_t>(stream));
+    if (st != SPARQ_OK) return st;
+    return conv_launch(xe, packed, &eff, &kNoPairPlain, acc, scale, out, nullptr, nullptr, xe + x_room,
+                       workspace_bytes - x_room, stream);
+}
+
 extern "C" sparq_status sparq_conv_gemm_u8(const uint8_t* x, const void* packed_w, const sparq_conv_desc* desc,
                                            const sparq_mode* mode, const float* factor, uint8_t* y,
                                            const sparq_mode* out_mode, void* workspace, size_t workspace_bytes,
