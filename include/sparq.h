@@ -27,7 +27,11 @@
  *     of one pixel; with odd C the last channel has an implicit zero partner.
  *   - Errors are reported by return code only.  Arguments are validated on
  *     the host before anything is enqueued; on an error nothing was launched.
- *   - No global state; calls on different streams may overlap.
+ *   - Calls on different streams and from different threads may overlap.  The
+ *     only state the library keeps between calls: the kernel-choice override
+ *     of sparq_set_tuning (a test hook, off by default), the per-GPU scratch of
+ *     sparq_conv_gemm_static_ws, and small caches of device properties.  The
+ *     environment is not read.
  */
 #ifndef SPARQ_H
 #define SPARQ_H
@@ -96,9 +100,7 @@ sparq_status sparq_pack_weights(const int8_t *w, const sparq_conv_desc *desc,
 
 /* Scratch the convolution may need for this descriptor and mode on the current
  * device: room for a trimmed, channel-padded copy of the input when C is not a
- * multiple of 16, plus M*N int32 partial sums for layers so small that the
- * reduction is split over several workgroups (used only when acc is NULL).
- * 0 for most layers.  The buffer is overwritten by every call that uses it;
+ * multiple of 16.  0 for most layers.  The buffer is overwritten by every call that uses it;
  * calls that share one workspace must not overlap. */
 size_t sparq_workspace_bytes(const sparq_conv_desc *desc, const sparq_mode *mode);
 
@@ -114,7 +116,7 @@ sparq_status sparq_conv_plan(const sparq_conv_desc *desc, const sparq_mode *mode
  * (zero outside the image), exact in int32, and optionally
  *   out[m][n] = (float)acc[m][n] * scale[n].
  * At least one of acc / out must be given; out requires scale.  x must be
- * 16-byte aligned, acc/out 16-byte aligned, packed_w as produced by
+ * 16-byte aligned, acc/out 16-byte aligned, scale 4-byte aligned, packed_w as produced by
  * sparq_pack_weights for the same desc.  workspace (256-byte aligned, at least
  * sparq_workspace_bytes() bytes) may be NULL when that size is 0; too small a
  * buffer returns SPARQ_EWORKSPACE before anything is launched.  Rejected with SPARQ_EINVAL when K = KH*KW*C
@@ -254,6 +256,19 @@ sparq_status sparq_conv_gemm_sparse24(const uint8_t *x, const void *packed,
                                       const sparq_conv_desc *desc, const sparq_mode *mode,
                                       int32_t *acc, const float *scale, float *out,
                                       void *workspace, size_t workspace_bytes, void *stream);
+
+/* Test and tuning hook: overrides, for the whole process and until changed
+ * again, which kernel and tiling the convolution entry points choose (the
+ * tests use it to drive every kernel over every shape; results never depend
+ * on it).  spec is a comma-separated list of key=value, NULL or "" clears it:
+ *   path=gather|patch        one of the two convolution kernels, where eligible
+ *   tile=128x128|128x256|128x512   gather kernel tile
+ *   patch_tn=64|128|256      input-patch kernel: output channels per tile
+ *   patch_ws=0|1             input-patch kernel: plain / wave-specialised form
+ * Anything else returns SPARQ_EINVAL and leaves the override as it was.
+ * Changing it while convolution calls are in flight on other threads makes
+ * those calls pick either setting. */
+sparq_status sparq_set_tuning(const char *spec);
 
 /* Static description of a status code. */
 const char *sparq_strerror(sparq_status status);

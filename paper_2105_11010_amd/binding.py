@@ -80,6 +80,8 @@ def _load() -> ctypes.CDLL:
     L.sparq_sparse24_workspace_bytes.restype = sz
     L.sparq_conv_gemm_sparse24.argtypes = [vp, vp, pd, pm, vp, vp, vp, vp, sz, vp]
     L.sparq_conv_gemm_sparse24.restype = ctypes.c_int
+    L.sparq_set_tuning.argtypes = [ctypes.c_char_p]
+    L.sparq_set_tuning.restype = ctypes.c_int
     L.sparq_strerror.argtypes = [ctypes.c_int]
     L.sparq_strerror.restype = ctypes.c_char_p
     return L
@@ -301,3 +303,8 @@ def sparq_conv_gemm_sparse24(x: torch.Tensor, packed: torch.Tensor, d: SparqConv
     _check(lib.sparq_conv_gemm_sparse24(_dev(x, torch.uint8, "x"), _dev(packed, torch.uint8, "packed"), ctypes.byref(d),
                                         ctypes.byref(m), _dev(acc, torch.int32, "acc"), _dev(scale, torch.float32, "scale"),
                                         _dev(out, torch.float32, "out"), ws_ptr, ws_bytes, _stream()), "sparq_conv_gemm_sparse24")
+
+
+def sparq_set_tuning(spec: Optional[str] = None) -> None:
+    """Test / tuning hook: force the kernel choice ("path=patch,patch_tn=128,patch_ws=1", ...); None clears it."""
+    _check(lib.sparq_set_tuning(spec.encode() if spec else None), "sparq_set_tuning")

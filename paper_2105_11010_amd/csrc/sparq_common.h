@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/sparq.h"
 #include "sparq_swar.h"
 
@@ -17,20 +19,25 @@ constexpr int kPadN = 256;        // packed output channels are padded to this
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 
 // ---- mode -----------------------------------------------------------------
+// A set of placements for w-bit windows is usable when the lookup tables of sparq_swar.h can be built from it:
+// every leading-one position 0..7 finds a placement, position 0 gets shift 0 (values below 2^w pass unchanged),
+// and no placement pushes a window past bit 7.
+inline bool placements_cover_a_byte(int w, uint32_t S) {
+    if (S & ~((2u << (8 - w)) - 1u)) return false;
+    if (trim_shift_for(0, w, S) != 0) return false;
+    for (int p = 1; p < 8; ++p)
+        if (trim_shift_for(p, w, S) > 8 - w) return false;
+    return true;
+}
+
 inline bool mode_valid(const sparq_mode* m) {
     if (!m) return false;
-    const int n = m->window_bits;
-    if (n == 8) return true;
-    if (n != 2 && n != 3 && n != 4) return false;
-    const uint32_t S = m->shift_mask;
-    if (S >> (8 - n + 1)) return false;
-    if (!(S & 1u) || !((S >> (8 - n)) & 1u)) return false;
-    if ((m->round_nearest | 1) != 1 || (m->pair | 1) != 1) return false;
-    if (m->pair) {
-        const uint32_t W = wide_shift_mask(n, S);
-        if (!(W & 1u) || !((W >> (8 - 2 * n)) & 1u)) return false;
-    }
-    return true;
+    if (m->window_bits == 8) return true;
+    if (m->window_bits < 2 || m->window_bits > 4) return false;
+    if ((unsigned)m->round_nearest > 1u || (unsigned)m->pair > 1u) return false;
+    if (!placements_cover_a_byte(m->window_bits, m->shift_mask)) return false;
+    // vSPARQ: a value whose partner is zero gets a window of twice the width (the whole byte for 4-bit windows)
+    return !m->pair || placements_cover_a_byte(2 * m->window_bits, wide_shift_mask(m->window_bits, m->shift_mask));
 }
 
 // Which compiled variant of the trim a mode needs.
@@ -203,17 +210,19 @@ inline int current_device_slot() {
     return dev < kMaxDevices ? dev : kMaxDevices - 1;
 }
 
-// Number of compute units of the current device (queried once per device).
+// Number of compute units of the current device (queried once per device; concurrent first calls both query).
 inline int device_cu_count() {
-    static int cus[kMaxDevices] = {};
+    static std::atomic<int> cus[kMaxDevices];
     const int slot = current_device_slot();
-    if (cus[slot] == 0) {
+    int n = cus[slot].load(std::memory_order_relaxed);
+    if (n == 0) {
         int dev = 0;
         hipDeviceProp_t prop;
         if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 256;
-        cus[slot] = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+        n = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+        cus[slot].store(n, std::memory_order_relaxed);
     }
-    return cus[slot];
+    return n;
 }
 
 // Implemented in sparq_elementwise.hip: trimmed copy of x with channels padded to Cp.
@@ -232,7 +241,5 @@ sparq_status launch_sparse24_expand_weights(const int8_t* vals, const uint8_t* i
 sparq_status launch_unpack_act(const void* packed, uint8_t* y, int64_t rows, int C, const sparq_mode* mode, int group,
                                hipStream_t stream);
 
-// Implemented in sparq_elementwise.hip: kernel-based clear of a 16-byte aligned buffer.
-sparq_status launch_zero(void* dst, size_t bytes, hipStream_t stream);
 
 }  // namespace sparq

@@ -13,6 +13,20 @@ using namespace sparq;
 
 namespace {
 
+// ---- the one test / tuning hook (sparq_set_tuning): process-wide overrides of the kernel choice ----
+struct Tuning {
+    int path = 0;             // 0: rules decide, 1: gather kernel, 2: input-patch kernel
+    char tile[16] = "";       // gather kernel tile "128x128" | "128x256" | "128x512"
+    int patch_tn = 0;         // input-patch kernel: output channels per tile (64 / 128 / 256), 0: rules decide
+    int patch_ws = -1;        // 1 / 0: wave-specialised / plain form, -1: rules decide
+};
+Tuning g_tuning;
+std::mutex g_tuning_mu;
+Tuning current_tuning() {
+    std::lock_guard<std::mutex> lock(g_tuning_mu);
+    return g_tuning;
+}
+
 struct TileEntry { const char* name; int tm, tn; TileLauncher fn; };
 const TileEntry kTiles[] = {
     {"128x128", 128, 128, launch_tile_128x128_w2x2_a1b2},
@@ -21,42 +35,41 @@ const TileEntry kTiles[] = {
 };
 
 // Tile choice: the widest output-channel tile the layer fills, so that an activation
-// is gathered and trimmed as few times as possible.  SPARQ_TILE=<name> (a tuning knob,
-// not part of the interface) forces one.
+// is gathered and trimmed as few times as possible; the tuning hook forces one.
 // A tile shape is usable only if all its weight loads stay inside the padded buffer.
 bool tile_fits(int tn, const ConvGeom& g) { return round_up(g.N, tn) <= g.Np; }
 
 // byte_output: the requantised uint8 output, which the 128x512 tile does not have.
-TileLauncher pick_tile(const ConvGeom& g, bool byte_output = false) {
-    if (const char* e = getenv("SPARQ_TILE"))
+TileLauncher pick_tile(const ConvGeom& g, const Tuning& tune, bool byte_output = false) {
+    if (tune.tile[0])
         for (const TileEntry& t : kTiles)
-            if (!strcmp(e, t.name) && tile_fits(t.tn, g) && !(byte_output && t.tn == 512)) return t.fn;
+            if (!strcmp(tune.tile, t.name) && tile_fits(t.tn, g) && !(byte_output && t.tn == 512)) return t.fn;
     if (g.N > 256 && tile_fits(512, g) && !byte_output) return kTiles[2].fn;
     if (g.N > 128) return kTiles[1].fn;
     return kTiles[0].fn;
 }
 
 // ---- input-patch kernel: eligibility and variant choice --------------------------------------
-struct PatchVariant { int tn, ac, cbs; PatchLauncher fn; PatchLauncher fn_split; PatchLauncher fn_ws; };   // fn_split / fn_ws: null if not built
+struct PatchVariant { int tn, ac, cbs; PatchLauncher fn; PatchLauncher fn_ws; };
 const PatchVariant kPatchVariants[] = {
-    {64, 2, 1, launch_patch_n64_a2c1, nullptr, launch_patch_ws_n64_a2c1},
-    {64, 4, 1, launch_patch_n64_a4c1, nullptr, launch_patch_ws_n64_a4c1},
-    {64, 8, 1, launch_patch_n64_a8c1, nullptr, launch_patch_ws_n64_a8c1},
-    {64, 12, 1, launch_patch_n64_a12c1, nullptr, launch_patch_ws_n64_a12c1},
-    {64, 4, 2, launch_patch_n64_a4c2, nullptr, launch_patch_ws_n64_a4c2},
-    {64, 8, 4, launch_patch_n64_a8c4, nullptr, launch_patch_ws_n64_a8c4},
-    {128, 2, 1, launch_patch_n128_a2c1, nullptr, launch_patch_ws_n128_a2c1},
-    {128, 4, 1, launch_patch_n128_a4c1, launch_patch_split_n128_a4c1, launch_patch_ws_n128_a4c1},
-    {128, 8, 1, launch_patch_n128_a8c1, launch_patch_split_n128_a8c1, launch_patch_ws_n128_a8c1},
-    {128, 12, 1, launch_patch_n128_a12c1, nullptr, launch_patch_ws_n128_a12c1},
-    {128, 4, 2, launch_patch_n128_a4c2, nullptr, launch_patch_ws_n128_a4c2},
-    {128, 8, 4, launch_patch_n128_a8c4, launch_patch_split_n128_a8c4, launch_patch_ws_n128_a8c4},
-    {256, 2, 1, launch_patch_n256_a2c1, nullptr, launch_patch_ws_n256_a2c1},
-    {256, 4, 1, launch_patch_n256_a4c1, nullptr, launch_patch_ws_n256_a4c1},
-    {256, 8, 1, launch_patch_n256_a8c1, nullptr, launch_patch_ws_n256_a8c1},
-    {256, 12, 1, launch_patch_n256_a12c1, nullptr, launch_patch_ws_n256_a12c1},
-    {256, 4, 2, launch_patch_n256_a4c2, nullptr, launch_patch_ws_n256_a4c2},
-    {256, 8, 4, launch_patch_n256_a8c4, nullptr, launch_patch_ws_n256_a8c4},
+    {64, 2, 1, launch_patch_n64_a2c1, launch_patch_ws_n64_a2c1},
+    {64, 4, 1, launch_patch_n64_a4c1, launch_patch_ws_n64_a4c1},
+    {64, 8, 1, launch_patch_n64_a8c1, launch_patch_ws_n64_a8c1},
+    {64, 12, 1, launch_patch_n64_a12c1, launch_patch_ws_n64_a12c1},
+    {64, 4, 2, launch_patch_n64_a4c2, launch_patch_ws_n64_a4c2},
+    {64, 8, 4, launch_patch_n64_a8c4, launch_patch_ws_n64_a8c4},
+    {128, 2, 1, launch_patch_n128_a2c1, launch_patch_ws_n128_a2c1},
+    {128, 4, 1, launch_patch_n128_a4c1, launch_patch_ws_n128_a4c1},
+    {128, 8, 1, launch_patch_n128_a8c1, launch_patch_ws_n128_a8c1},
+    {128, 12, 1, launch_patch_n128_a12c1, launch_patch_ws_n128_a12c1},
+    {128, 4, 2, launch_patch_n128_a4c2, launch_patch_ws_n128_a4c2},
+    {128, 8, 4, launch_patch_n128_a8c4, launch_patch_ws_n128_a8c4},
+    {256, 2, 1, launch_patch_n256_a2c1, launch_patch_ws_n256_a2c1},
+    {256, 4, 1, launch_patch_n256_a4c1, launch_patch_ws_n256_a4c1},
+    {256, 8, 1, launch_patch_n256_a8c1, launch_patch_ws_n256_a8c1},
+    {256, 12, 1, launch_patch_n256_a12c1, launch_patch_ws_n256_a12c1},
+    {256, 4, 2, launch_patch_n256_a4c2, launch_patch_ws_n256_a4c2},
+    {256, 8, 4, launch_patch_n256_a8c4, launch_patch_ws_n256_a8c4},
 };
 
 // Largest patch (in pixels) any tile of this geometry needs.  Tile positions repeat relative to the
@@ -137,8 +150,8 @@ bool plan_patch(const ConvGeom& g, PatchGeom* pg, int* npix, int* ac, int* cbs) 
 //   holds one workgroup per CU anyway (strided 3x3 layers on large images) when the layer is wide and fills the chip.
 //   128 otherwise: two plain workgroups per CU that hide each other's latencies for 1x1 layers with many tiles,
 //   wave-specialised for multi-tap layers and for layers with no more tiles than CUs.
-// SPARQ_PATCH_TN=<n> and SPARQ_PATCH_WS=0|1 (tuning knobs) force the choice.
-const PatchVariant* pick_patch(const ConvGeom& g, int ac, int cbs, int npix, bool forced, bool* ws) {
+// The tuning hook forces tile width and form.
+const PatchVariant* pick_patch(const ConvGeom& g, const Tuning& tune, int ac, int cbs, int npix, bool forced, bool* ws) {
     const int64_t tiles_m = (g.M + kPatchTM - 1) / kPatchTM;
     const int64_t t128 = tiles_m * ((g.N + 127) / 128), t256 = tiles_m * ((g.N + 255) / 256);
     const int cus = device_cu_count();
@@ -151,11 +164,8 @@ const PatchVariant* pick_patch(const ConvGeom& g, int ac, int cbs, int npix, boo
         else if (g.N < 256 && t128 >= cus && !forced) return nullptr;   // narrow: gather kernel
     }
     *ws = tn != 128 || g.KH * g.KW > 1 || t128 <= cus;
-    if (const char* e = getenv("SPARQ_PATCH_TN")) {
-        const int v = atoi(e);
-        if ((v == 64 || v == 128 || v == 256) && tile_fits(v, g)) tn = v;
-    }
-    if (const char* e = getenv("SPARQ_PATCH_WS")) *ws = atoi(e) != 0;
+    if ((tune.patch_tn == 64 || tune.patch_tn == 128 || tune.patch_tn == 256) && tile_fits(tune.patch_tn, g)) tn = tune.patch_tn;
+    if (tune.patch_ws >= 0) *ws = tune.patch_ws != 0;
     const bool strided_1x1 = g.KH == 1 && g.KW == 1 && (g.sh > 1 || g.sw > 1);    // pixel remap: staging wavefronts only
     if (strided_1x1) *ws = true;
     for (const PatchVariant& v : kPatchVariants)
@@ -165,24 +175,6 @@ const PatchVariant* pick_patch(const ConvGeom& g, int ac, int cbs, int npix, boo
             return &v;
         }
     return nullptr;
-}
-
-// Split reduction: when a layer has far fewer tiles than the chip has room for workgroups, a
-// tile's channel blocks are spread over 2^k workgroups that add their int32 partial sums with
-// atomics (exact: integer addition commutes).  SPARQ_SPLIT=<k> (a tuning knob) forces k.
-int pick_split_log2(const ConvGeom& g, const PatchVariant& v, int ncb) {
-    if (!v.fn_split) return 0;
-    const int64_t tiles = (g.M + kPatchTM - 1) / kPatchTM * ((g.N + v.tn - 1) / v.tn);
-    const int64_t slots = (int64_t)device_cu_count() * 2;
-    int lg = 0;
-    // worth it only while the chip stays at most half full: the cleared buffer and the extra
-    // dequantisation pass cost two more small launches
-    while (lg < 3 && ncb % (2 << lg) == 0 && tiles * (2 << lg) * 2 <= slots) ++lg;
-    if (const char* e = getenv("SPARQ_SPLIT")) {
-        const int v = atoi(e);
-        if (v >= 0 && v <= 3 && ncb % (1 << v) == 0) lg = v;
-    }
-    return lg;
 }
 
 // 1x1 layers with a long reduction have nothing to reuse between taps; when they also
@@ -201,56 +193,88 @@ struct ConvPlan {
     bool patch = false;
     const PatchVariant* variant = nullptr;
     PatchGeom pg{};
-    int npix = 0, ac = 0, cbs = 0, split_log2 = 0;
+    int npix = 0, ac = 0, cbs = 0;
     bool ws = false;            // wave-specialised form of the patch kernel
     size_t pad_bytes = 0;       // channel-padded copy of x (channel counts that are not a multiple of 16)
-    size_t split_bytes = 0;     // int32 partial sums of a split reduction when the caller passes no acc
 };
 
-ConvPlan make_plan(const ConvGeom& g) {
+ConvPlan make_plan(const ConvGeom& g, const Tuning& tune) {
     ConvPlan pl;
     if (g.fold) {               // at most 4 channels: 4-channel padded copy, pixel-folded, gather kernel
         pl.pad_bytes = (size_t)round_up((int64_t)g.B * g.H * g.W * 4, 256);
         return pl;
     }
     if (g.Cp != g.C) pl.pad_bytes = (size_t)round_up((int64_t)g.B * g.H * g.W * g.Cp, 256);
-    const char* path = getenv("SPARQ_PATH");
-    const bool force_gather = path && !strcmp(path, "gather"), force_patch = path && !strcmp(path, "patch");
+    const bool force_gather = tune.path == 1, force_patch = tune.path == 2;
     ConvGeom gk = g;
     gk.C = gk.Cp;                                                // what the kernel sees after the padding pre-pass
     if (!force_gather && (force_patch || !prefer_gather(g)) && plan_patch(gk, &pl.pg, &pl.npix, &pl.ac, &pl.cbs)) {
-        pl.variant = pick_patch(g, pl.ac, pl.cbs, pl.npix, force_patch, &pl.ws);
-        if (pl.variant) {
-            pl.patch = true;
-            pl.split_log2 = pl.pg.rm_wo ? 0 : pick_split_log2(g, *pl.variant, g.Cq / kStepK / pl.cbs);   // (strided 1x1: staging wavefronts only)
-            if (pl.split_log2) pl.split_bytes = (size_t)round_up(g.M * g.N * 4, 256);
-        }
+        pl.variant = pick_patch(g, tune, pl.ac, pl.cbs, pl.npix, force_patch, &pl.ws);
+        pl.patch = pl.variant != nullptr;
     }
     return pl;
 }
 
 }  // namespace
 
+extern "C" sparq_status sparq_set_tuning(const char* spec) {
+    Tuning t;
+    const char* p = spec ? spec : "";
+    while (*p) {
+        const char* end = strchr(p, ',');
+        const size_t len = end ? (size_t)(end - p) : strlen(p);
+        char item[48];
+        if (len == 0 || len >= sizeof(item)) return SPARQ_EINVAL;
+        memcpy(item, p, len);
+        item[len] = 0;
+        char* eq = strchr(item, '=');
+        if (!eq) return SPARQ_EINVAL;
+        *eq = 0;
+        const char* key = item;
+        const char* val = eq + 1;
+        if (!strcmp(key, "path")) {
+            if (!strcmp(val, "gather")) t.path = 1;
+            else if (!strcmp(val, "patch")) t.path = 2;
+            else return SPARQ_EINVAL;
+        } else if (!strcmp(key, "tile")) {
+            if (strcmp(val, "128x128") && strcmp(val, "128x256") && strcmp(val, "128x512")) return SPARQ_EINVAL;
+            strcpy(t.tile, val);
+        } else if (!strcmp(key, "patch_tn")) {
+            t.patch_tn = atoi(val);
+            if (t.patch_tn != 64 && t.patch_tn != 128 && t.patch_tn != 256) return SPARQ_EINVAL;
+        } else if (!strcmp(key, "patch_ws")) {
+            if (strcmp(val, "0") && strcmp(val, "1")) return SPARQ_EINVAL;
+            t.patch_ws = val[0] - '0';
+        } else {
+            return SPARQ_EINVAL;
+        }
+        p += len + (end ? 1 : 0);
+    }
+    std::lock_guard<std::mutex> lock(g_tuning_mu);
+    g_tuning = t;
+    return SPARQ_OK;
+}
+
 extern "C" size_t sparq_workspace_bytes(const sparq_conv_desc* desc, const sparq_mode* mode) {
     ConvGeom g;
     if (!conv_geom(desc, &g) || !mode_valid(mode)) return 0;
-    const ConvPlan pl = make_plan(g);
-    return pl.pad_bytes + pl.split_bytes;
+    return make_plan(g, current_tuning()).pad_bytes;
 }
 
 extern "C" sparq_status sparq_conv_plan(const sparq_conv_desc* desc, const sparq_mode* mode, char* text, size_t text_bytes) {
     ConvGeom g;
     if (!text || text_bytes == 0 || !conv_geom(desc, &g) || !mode_valid(mode)) return SPARQ_EINVAL;
-    const ConvPlan pl = make_plan(g);
+    const Tuning tune = current_tuning();
+    const ConvPlan pl = make_plan(g, tune);
     if (pl.patch) {
-        snprintf(text, text_bytes, "conv_patch_kernel tile=128x%d chunks=%d unit_channels=%d split=%d patch_pixels=%d%s%s",
-                 pl.variant->tn, pl.ac, 64 * pl.cbs, 1 << pl.split_log2, pl.npix,
-                 (pl.ws && !pl.split_log2) ? " wave_specialised" : "", pl.pad_bytes ? " padded_copy" : "");
+        snprintf(text, text_bytes, "conv_patch_kernel tile=128x%d chunks=%d unit_channels=%d patch_pixels=%d%s%s",
+                 pl.variant->tn, pl.ac, 64 * pl.cbs, pl.npix, pl.ws ? " wave_specialised" : "",
+                 pl.pad_bytes ? " padded_copy" : "");
     } else {
         const char* name = "?";
         ConvGeom gt = g.fold ? folded_view(g) : g;
         gt.Np = g.Np;
-        const TileLauncher fn = pick_tile(gt);
+        const TileLauncher fn = pick_tile(gt, tune);
         for (const TileEntry& t : kTiles)
             if (t.fn == fn) name = t.name;
         snprintf(text, text_bytes, "conv_gemm_kernel tile=%s%s%s", name, pl.pad_bytes ? " padded_copy" : "",
@@ -279,12 +303,12 @@ sparq_status conv_launch(const uint8_t* x, const void* packed_w, const sparq_con
                            out_mode->round_nearest == mode->round_nearest && out_mode->pair == mode->pair;
     bool fused_trim = same_mode && g.N % 4 == 0;
     if (!aligned(x, 16) || !aligned(packed_w, 256) || (acc && !aligned(acc, 16)) || (out && !aligned(out, 16)) ||
-        (y && !aligned(y, 16)) || (scale && !aligned(scale, 16)))
+        (y && !aligned(y, 16)) || (scale && !aligned(scale, 4)))
         return SPARQ_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const ConvPlan pl = make_plan(g);
-    const bool split = pl.patch && pl.split_log2 > 0;
-    const size_t need = pl.pad_bytes + ((split && !acc) ? pl.split_bytes : 0);   // (y: acc is null)
+    const Tuning tune = current_tuning();
+    const ConvPlan pl = make_plan(g, tune);
+    const size_t need = pl.pad_bytes;
     if (need) {
         if (!workspace || !aligned(workspace, 256)) return SPARQ_EINVAL;
         if (workspace_bytes < need) return SPARQ_EWORKSPACE;
@@ -315,7 +339,7 @@ sparq_status conv_launch(const uint8_t* x, const void* packed_w, const sparq_con
         p.luts = make_luts(8, 1);
         ConvGeom ft = f;
         ft.Np = g.Np;
-        const sparq_status stf = pick_tile(ft, y != nullptr)(kTrimNone, p, s);
+        const sparq_status stf = pick_tile(ft, tune, y != nullptr)(kTrimNone, p, s);
         if (stf != SPARQ_OK || !trim_y) return stf;
         return sparq_trim(y, y, g.M, g.N, out_mode, stream);
     }
@@ -338,8 +362,7 @@ sparq_status conv_launch(const uint8_t* x, const void* packed_w, const sparq_con
         return sparq_trim(y, y, g.M, g.N, out_mode, stream);
     };
 
-    // Preferred: the input-patch kernel (activations loaded and trimmed once per tile and channel
-    // block).  SPARQ_PATH=gather|patch (a tuning knob, not part of the interface) forces one of the two kernels.
+    // Preferred: the input-patch kernel (activations loaded and trimmed once per tile and channel block).
     if (pl.patch) {
         PatchParams q{};
         q.x = xin;
@@ -350,8 +373,7 @@ sparq_status conv_launch(const uint8_t* x, const void* packed_w, const sparq_con
         q.w_bytes = (uint32_t)((size_t)g.Kp * g.Np);
         q.N = g.N; q.Np = g.Np; q.C = g.Cp;
         q.ksteps_tap = g.Cq / kStepK;
-        q.ncb = (q.ksteps_tap / pl.cbs) >> pl.split_log2;
-        q.split_log2 = pl.split_log2;
+        q.ncb = q.ksteps_tap / pl.cbs;
         q.nsteps = g.KH * g.KW * pl.cbs;
         q.g = pl.pg;
         q.luts = make_luts(mode->window_bits, mode->shift_mask);
@@ -363,7 +385,7 @@ sparq_status conv_launch(const uint8_t* x, const void* packed_w, const sparq_con
         // (A layer that would take the plain form takes the wave-specialised one here: that costs a few per cent,
         // the separate trim pass over y it avoids costs more.)
         bool use_ws = pl.ws;
-        if (trim_y && !fused_trim && !split && kind == kTrimNone && mode->window_bits == 8 && g.N % 4 == 0 &&
+        if (trim_y && !fused_trim && kind == kTrimNone && mode->window_bits == 8 && g.N % 4 == 0 &&
             g.Cp == g.C && pl.variant->fn_ws) {
             use_ws = true;
             pkind = trim_kind(out_mode);
@@ -372,17 +394,7 @@ sparq_status conv_launch(const uint8_t* x, const void* packed_w, const sparq_con
             pfused = true;
         }
         q.trim_out = pfused ? 1 : 0;
-        if (split) {
-            // partial sums are added into a cleared int32 buffer; the fp32 output is a second pass over it
-            int32_t* sum = acc ? acc : reinterpret_cast<int32_t*>(static_cast<uint8_t*>(workspace) + pl.pad_bytes);
-            sparq_status st = launch_zero(sum, (size_t)round_up(g.M * g.N * 4, 16), s);
-            if (st != SPARQ_OK) return st;
-            q.acc = sum; q.scale = nullptr; q.out = nullptr; q.out_u8 = nullptr;
-            st = pl.variant->fn_split(kind, q, pl.npix, s);
-            if (st == SPARQ_OK && out) st = sparq_dequant(sum, scale, out, g.M, g.N, stream);
-            if (st == SPARQ_OK && y) st = sparq_requant(sum, scale, y, g.M, g.N, stream);
-            if (st != SPARQ_EUNSUPPORTED) return finish(st, false);
-        } else {
+        {
             const PatchLauncher fn = use_ws ? pl.variant->fn_ws : pl.variant->fn;
             const sparq_status st = fn(pkind, q, pl.npix, s);
             if (st != SPARQ_EUNSUPPORTED) return finish(st, pfused);
@@ -407,7 +419,7 @@ sparq_status conv_launch(const uint8_t* x, const void* packed_w, const sparq_con
     p.rcp_kw = 1.0f / (float)g.KW;
     p.luts = make_luts(mode->window_bits, mode->shift_mask);
 
-    return finish(pick_tile(g, y != nullptr)(kind, p, s), fused_trim);
+    return finish(pick_tile(g, tune, y != nullptr)(kind, p, s), fused_trim);
 }
 
 }  // namespace
@@ -453,8 +465,7 @@ extern "C" sparq_status sparq_conv_gemm_static_ws(const uint8_t* x, const void* 
     if (!acc && !out) return SPARQ_EINVAL;
     ConvGeom g;
     if (!conv_geom(desc, &g) || !mode_valid(mode)) return SPARQ_EINVAL;
-    const ConvPlan pl = make_plan(g);
-    const size_t need = pl.pad_bytes + pl.split_bytes;
+    const size_t need = make_plan(g, current_tuning()).pad_bytes;
     if (need > (size_t)SPARQ_STATIC_WORKSPACE_BYTES) return SPARQ_EWORKSPACE;
     void* ws = nullptr;
     if (need) {
@@ -462,7 +473,7 @@ extern "C" sparq_status sparq_conv_gemm_static_ws(const uint8_t* x, const void* 
         if (st != SPARQ_OK) return st;
     }
     // Every byte of the scratch a call reads it has written itself first (the padded copy is written whole by the
-    // trim pass, split sums are cleared by a kernel), so the last call's contents never show.
+    // trim pass), so the last call's contents never show.
     return conv_launch(x, packed_w, desc, mode, acc, scale, out, nullptr, nullptr, ws, need, stream);
 }
 

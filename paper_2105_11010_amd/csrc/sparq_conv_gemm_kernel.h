@@ -18,6 +18,8 @@
 // activation is trimmed once when its tile is loaded and then reused for all
 // output channels the workgroup covers.
 #pragma once
+#include <atomic>
+
 #include "sparq_common.h"
 
 namespace sparq {
@@ -381,16 +383,14 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
 
 template <class Cfg, int KIND>
 sparq_status launch_cfg(const GemmParams& p, hipStream_t s) {
-    static bool attr_set_dev[kMaxDevices] = {};      // per device
+    static std::atomic<bool> attr_set_dev[kMaxDevices];      // per device; concurrent callers at worst repeat the call
     const int slot = current_device_slot();
-    bool& attr_set = attr_set_dev[slot];
-    if (slot == kMaxDevices - 1) attr_set = false;
     auto kern = conv_gemm_kernel<Cfg, KIND>;
-    if (!attr_set) {
+    if (slot == kMaxDevices - 1 || !attr_set_dev[slot].load(std::memory_order_relaxed)) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 Cfg::kLdsBytes) != hipSuccess)
             return SPARQ_ELAUNCH;
-        attr_set = true;
+        attr_set_dev[slot].store(true, std::memory_order_relaxed);
     }
     if (p.out_u8 && !Cfg::kByteOutput) return SPARQ_EUNSUPPORTED;
     GemmParams q = p;

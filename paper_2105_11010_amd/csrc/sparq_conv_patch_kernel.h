@@ -23,6 +23,7 @@
 // and runs at a much lower rate than the multipliers (Section 5); staging the trimmed patch once
 // and reusing it for all taps and all output channels of the tile is that arrangement.
 #pragma once
+#include <atomic>
 #include <type_traits>
 
 #include "sparq_common.h"
@@ -47,11 +48,10 @@ struct PatchParams {
     uint32_t x_bytes, w_bytes;
     int N, Np, C;
     int ncb;                 // channel blocks (units) per work item
-    int split_log2;          // a tile's channel blocks are spread over 2^split_log2 work items (split reduction)
     int ksteps_tap;          // 64-byte steps per filter tap in the packed weights
     int nsteps;              // steps per unit = KH * KW * CBS
     int plane_stride;        // bytes between the 16-channel planes of a patch buffer
-    int tiles_m, tiles_n;    // tiles_n counts work items: output-channel tiles x reduction splits
+    int tiles_m, tiles_n;
     PatchGeom g;
     TrimLuts luts;
 };
@@ -61,15 +61,13 @@ constexpr uint32_t kPatchInvalidOffset = 0x80000000u;   // beyond any buffer thi
 
 // TN output channels per workgroup, WGM x WGN wavefronts, AC 16-byte patch chunks per lane and
 // unit, CBS * 64 input channels per unit, WPC resident workgroups per CU the register budget allows.
-// SPLITK: the variant for split reductions (partial sums added to acc with atomics).
 // WS: wave-specialised variant -- wavefronts 4..7 load, trim and stage the patches, wavefronts 0..3 only read
 // fragments and weights and multiply.  A wavefront's loads return in order, so in the plain variant a weight wait
 // also waits for every older (slow, HBM) activation load; with separate wavefronts it does not, and the trim
 // arithmetic issues from other wavefronts while the matrix instructions run.
-template <int TN, int WGM, int WGN, int AC, int CBS, int WPC, bool SPLITK = false, bool WS = false>
+template <int TN, int WGM, int WGN, int AC, int CBS, int WPC, bool WS = false>
 struct PatchCfg {
     static constexpr bool kWaveSpecialised = WS;            // four more wavefronts do the loading, trimming and staging
-    static constexpr bool kSplitK = SPLITK;                  // results are added to acc with atomics (split reduction)
     static constexpr int kTM = kPatchTM, kTN = TN, kWGM = WGM, kWGN = WGN, kAC = AC, kCBS = CBS, kWgPerCu = WPC;
     static constexpr int kMathThreads = 64 * WGM * WGN;
     static constexpr int kStageThreads = 256;
@@ -116,7 +114,6 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
     const int ntiles = p.tiles_m * p.tiles_n;
     const int grid = (int)gridDim.x;
     const int buf_bytes = PL * p.plane_stride;
-    const int split_mask = (1 << p.split_log2) - 1;
     const __amdgpu_buffer_rsrc_t xrsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.x), 0, (int)p.x_bytes, 0x00020000);
 
@@ -130,13 +127,12 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
     v4u a_reg[AC];                                // requested chunks (of the unit after next)
 
     // load cursor: the unit whose chunks are requested next; its tile's patch, uniform
-    int l_tile = (int)blockIdx.x, l_cb = 0, l_cb0 = 0;   // l_cb0: first channel block of the work item
+    int l_tile = (int)blockIdx.x, l_cb = 0;
     TilePatch lt;
     int stage_npix = 0;                           // patch size of the unit whose chunks are staged next
     auto load_tile_patch = [&]() __attribute__((always_inline)) {
         const bool live = l_tile < ntiles;
         const int tm = live ? l_tile / p.tiles_n : 0;
-        l_cb0 = ((l_tile - tm * p.tiles_n) & split_mask) * p.ncb;
         const TilePatch t = tile_patch(g, tm * kPatchTM);
         lt.v0 = __builtin_amdgcn_readfirstlane(t.v0);
         lt.xlo = __builtin_amdgcn_readfirstlane(t.xlo);
@@ -153,7 +149,7 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
     };
     auto load_chunk = [&](int i) __attribute__((always_inline)) {
         const int pix = my_pix + i * (NT / PL);
-        const int ch = (l_cb0 + l_cb) * Cfg::kCB + my_c;
+        const int ch = l_cb * Cfg::kCB + my_c;
         // only the staging wavefronts of the wave-specialised form handle the pixel remap of strided 1x1 layers
         uint32_t off = patch_pixel_offset_u32<WS>(g, lt, pix, p.C, kPatchInvalidOffset);
         off = (ch < p.C) ? off : kPatchInvalidOffset;            // a tap's channel padding reads as zero
@@ -230,8 +226,8 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
     const int grid_n = grid % p.tiles_n;
     int b_s = 0, b_cb = 0, b_tn = (int)blockIdx.x % p.tiles_n;
     auto next_b_offset = [&]() __attribute__((always_inline)) -> int {
-        const int kidx = (b_s / CBS) * p.ksteps_tap + ((b_tn & split_mask) * p.ncb + b_cb) * CBS + (b_s % CBS);
-        const int off = (b_tn >> p.split_log2) * TN * kChunk + kidx * 2 * w_half;
+        const int kidx = (b_s / CBS) * p.ksteps_tap + b_cb * CBS + (b_s % CBS);
+        const int off = b_tn * TN * kChunk + kidx * 2 * w_half;
         ++b_s;
         const bool ws = b_s == p.nsteps;
         b_s = ws ? 0 : b_s;
@@ -412,29 +408,10 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
             // Register v of fragment (i, j) is pixel 8*(v/4) + 4*lhi + v%4, channel l32: each store
             // instruction writes two full 128-byte runs of consecutive channels.
             const int64_t m0 = (int64_t)c_tm * kPatchTM;
-            const int n0 = (c_tn >> p.split_log2) * TN;
-            const int corr_mul = (c_tn & split_mask) == 0 ? 128 : 0;       // only the first split adds the offset term
+            const int n0 = c_tn * TN;
+            constexpr int corr_mul = 128;
             const float* scale_or_dummy = (p.out || p.out_u8) ? p.scale : reinterpret_cast<const float*>(p.colsum);
-            if constexpr (Cfg::kSplitK) {
-                // partial sums of a split reduction: int32 adds commute, the result is exact
-#pragma unroll
-                for (int j = 0; j < FN; ++j) {
-                    const int n = n0 + wn * Cfg::kWTN + j * 32 + l32;
-                    if (n >= p.N) continue;
-                    const int32_t corr = p.colsum[n] * corr_mul;
-#pragma unroll
-                    for (int i = 0; i < FM; ++i) {
-                        const int64_t mb = m0 + wm * Cfg::kWTM + i * 32 + 4 * lhi;
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) {
-                            const int64_t m = mb + 8 * (v / 4) + (v % 4);
-                            if (m >= g.M) continue;
-                            __hip_atomic_fetch_add(p.acc + m * p.N + n, c[i][j][v] + corr, __ATOMIC_RELAXED,
-                                                   __HIP_MEMORY_SCOPE_AGENT);
-                        }
-                    }
-                }
-            } else {
+            {
                 // Buffer stores relative to the tile's first row: the lane's part of the offset is computed
                 // once, every row adds a uniform multiple of the row pitch, and rows past M or channels
                 // past N fall outside the buffer's range and are dropped by the hardware (no per-row
@@ -559,7 +536,6 @@ sparq_status launch_patch_cfg(const PatchParams& p, int npix_max, hipStream_t s)
     PatchParams q = p;
     q.plane_stride = patch_plane_stride(npix_max, Cfg::kPlanes);
     const int lds_bytes = 2 * Cfg::kPlanes * q.plane_stride + kChunk;     // two patch buffers + the dummy chunk
-    if ((p.split_log2 != 0) != Cfg::kSplitK) return SPARQ_EUNSUPPORTED;
     if (p.g.rm_wo && !Cfg::kWaveSpecialised) return SPARQ_EUNSUPPORTED;
     if (!p.trim_in && !Cfg::kWaveSpecialised && KIND != kTrimNone) return SPARQ_EUNSUPPORTED;
     if ((int64_t)p.N * 4 * kPatchTM >= 0x7FFFFFFF) return SPARQ_EUNSUPPORTED;   // 32-bit offsets inside a tile of results
@@ -567,16 +543,17 @@ sparq_status launch_patch_cfg(const PatchParams& p, int npix_max, hipStream_t s)
         ((q.nsteps - Cfg::kUnrolled) & 1))
         return SPARQ_EUNSUPPORTED;
     auto kern = conv_patch_kernel<Cfg, KIND>;
-    static int lds_set_dev[kMaxDevices] = {};        // largest dynamic LDS size enabled so far, per device
-    int& lds_set = lds_set_dev[current_device_slot()];
-    if (lds_bytes > lds_set || current_device_slot() == kMaxDevices - 1) {
+    // largest dynamic LDS size enabled so far, per device (relaxed atomics: concurrent callers at worst repeat the call)
+    static std::atomic<int> lds_set_dev[kMaxDevices];
+    std::atomic<int>& lds_set = lds_set_dev[current_device_slot()];
+    if (lds_bytes > lds_set.load(std::memory_order_relaxed) || current_device_slot() == kMaxDevices - 1) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 lds_bytes) != hipSuccess)
             return SPARQ_ELAUNCH;
-        lds_set = lds_bytes;
+        lds_set.store(lds_bytes, std::memory_order_relaxed);
     }
     q.tiles_m = (p.g.M + kPatchTM - 1) / kPatchTM;
-    q.tiles_n = ((p.N + Cfg::kTN - 1) / Cfg::kTN) << p.split_log2;
+    q.tiles_n = (p.N + Cfg::kTN - 1) / Cfg::kTN;
     const int64_t tiles = (int64_t)q.tiles_m * q.tiles_n;
     if (tiles > 0x7FFFFFFF) return SPARQ_EUNSUPPORTED;
     int per_cu = kLdsPerCu / lds_bytes;
@@ -591,14 +568,12 @@ template <class Cfg>
 sparq_status launch_patch_kind(TrimKind kind, const PatchParams& p, int npix_max, hipStream_t s) {
     switch (kind) {
         case kTrimNone: return launch_patch_cfg<Cfg, kTrimNone>(p, npix_max, s);
-#ifndef SPARQ_DEV_FEW_KINDS
         case kTrimFloor: return launch_patch_cfg<Cfg, kTrimFloor>(p, npix_max, s);
         case kTrimFloorPair: return launch_patch_cfg<Cfg, kTrimFloorPair>(p, npix_max, s);
         case kTrimFloorPairWide: return launch_patch_cfg<Cfg, kTrimFloorPairWide>(p, npix_max, s);
         case kTrimRound: return launch_patch_cfg<Cfg, kTrimRound>(p, npix_max, s);
         case kTrimRound4: return launch_patch_cfg<Cfg, kTrimRound4>(p, npix_max, s);
         case kTrimRoundPairWide: return launch_patch_cfg<Cfg, kTrimRoundPairWide>(p, npix_max, s);
-#endif
         case kTrimRoundPair4: return launch_patch_cfg<Cfg, kTrimRoundPair4>(p, npix_max, s);
         default: return SPARQ_EUNSUPPORTED;
     }
@@ -625,9 +600,6 @@ SPARQ_DECLARE_PATCH(launch_patch_ws_n256_a8c1);
 SPARQ_DECLARE_PATCH(launch_patch_ws_n256_a12c1);
 SPARQ_DECLARE_PATCH(launch_patch_ws_n256_a4c2);
 SPARQ_DECLARE_PATCH(launch_patch_ws_n256_a8c4);
-SPARQ_DECLARE_PATCH(launch_patch_split_n128_a4c1);
-SPARQ_DECLARE_PATCH(launch_patch_split_n128_a8c1);
-SPARQ_DECLARE_PATCH(launch_patch_split_n128_a8c4);
 SPARQ_DECLARE_PATCH(launch_patch_n64_a12c1);
 SPARQ_DECLARE_PATCH(launch_patch_n128_a12c1);
 SPARQ_DECLARE_PATCH(launch_patch_n256_a12c1);

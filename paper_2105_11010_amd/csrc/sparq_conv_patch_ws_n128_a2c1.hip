@@ -4,5 +4,5 @@
 #include "sparq_conv_patch_kernel.h"
 
 namespace sparq {
-SPARQ_DECLARE_PATCH(launch_patch_ws_n128_a2c1) { return launch_patch_kind<PatchCfg<128, 2, 2, 2, 1, 1, false, true>>(kind, p, npix_max, s); }
+SPARQ_DECLARE_PATCH(launch_patch_ws_n128_a2c1) { return launch_patch_kind<PatchCfg<128, 2, 2, 2, 1, 1, true>>(kind, p, npix_max, s); }
 }  // namespace sparq

@@ -4,5 +4,5 @@
 #include "sparq_conv_patch_kernel.h"
 
 namespace sparq {
-SPARQ_DECLARE_PATCH(launch_patch_ws_n256_a8c1) { return launch_patch_kind<PatchCfg<256, 1, 4, 8, 1, 1, false, true>>(kind, p, npix_max, s); }
+SPARQ_DECLARE_PATCH(launch_patch_ws_n256_a8c1) { return launch_patch_kind<PatchCfg<256, 1, 4, 8, 1, 1, true>>(kind, p, npix_max, s); }
 }  // namespace sparq

@@ -262,22 +262,6 @@ extern "C" sparq_status sparq_trim(const uint8_t* x, uint8_t* y, int64_t rows, i
     return launch_status();
 }
 
-__global__ __launch_bounds__(kEwThreads) void zero_kernel(int4* __restrict__ dst, int64_t n_vec) {
-    const int64_t stride = (int64_t)gridDim.x * kEwThreads;
-    for (int64_t i = (int64_t)blockIdx.x * kEwThreads + threadIdx.x; i < n_vec; i += stride) dst[i] = make_int4(0, 0, 0, 0);
-}
-
-namespace sparq {
-// Clears `bytes` (a multiple of 16) at a 16-byte aligned address with a kernel, so that callers
-// may capture the launch sequence.
-sparq_status launch_zero(void* dst, size_t bytes, hipStream_t s) {
-    const int64_t n_vec = (int64_t)(bytes / 16);
-    if (n_vec == 0) return SPARQ_OK;
-    zero_kernel<<<ew_grid(n_vec, kEwThreads * 4), kEwThreads, 0, s>>>(static_cast<int4*>(dst), n_vec);
-    return launch_status();
-}
-}  // namespace sparq
-
 extern "C" sparq_status sparq_dequant(const int32_t* acc, const float* scale, float* out, int64_t M, int32_t N,
                                       void* stream) {
     if (M < 0 || N <= 0) return SPARQ_EINVAL;

@@ -70,12 +70,11 @@ inline void fill_tables(int n, uint32_t S, uint32_t* a_lo, uint32_t* a_hi, uint3
     *b_lo = (uint32_t)B; *b_hi = (uint32_t)(B >> 32);
 }
 
-// Shifts t for which a 2n-bit window may sit at t: both halves (t and t+n) must be options.
+// Placements of the 2n-bit window a value gets when its partner is zero: the two n-bit multipliers of Eq. 4
+// serve it as a high and a low half, so t is a placement when t and t + n both are n-bit placements (and the
+// window stays inside the byte: t <= 8 - 2n).
 inline uint32_t wide_shift_mask(int n, uint32_t S) {
-    uint32_t w = 0;
-    for (int t = 0; t + 2 * n <= 8; ++t)
-        if (((S >> t) & 1u) && ((S >> (t + n)) & 1u)) w |= 1u << t;
-    return w;
+    return S & (S >> n) & ((2u << (8 - 2 * n)) - 1u);
 }
 
 inline TrimLuts make_luts(int n, uint32_t S) {

@@ -32,8 +32,6 @@ def lib():
 
 
 def plan(lib, l, mode=None):
-    for k in ("SPARQ_PATH", "SPARQ_PATCH_TN", "SPARQ_PATCH_WS", "SPARQ_SPLIT", "SPARQ_TILE"):
-        os.environ.pop(k, None)
     d = Desc(l.B, l.H, l.W, l.C, l.N, l.KH, l.KW, l.stride[0], l.stride[1], l.pad[0], l.pad[1])
     m = Mode(*(mode or l.mode).astuple())
     buf = ctypes.create_string_buffer(256)
@@ -55,11 +53,8 @@ def test_every_workload_layer_has_a_consistent_plan(lib, cfg, layer):
         assert "padded_copy" in text and ws >= pixels * ((layer.C + 15) // 16 * 16)
     else:
         assert "padded_copy" not in text
-    if "split=1" in text or text.startswith("conv_gemm_kernel"):
-        if layer.C % 16 == 0:
-            assert ws == 0                                            # nothing to stage, nothing to sum
-    else:
-        assert ws >= layer.M * layer.N * 4                           # room for the split reduction's partial sums
+    if layer.C % 16 == 0:
+        assert ws == 0                                                # nothing to stage
     assert packed >= layer.K * layer.N
 
 
@@ -69,6 +64,25 @@ def test_plan_of_the_headline_shapes(lib):
     assert text.startswith("conv_patch_kernel tile=128x256") and "wave_specialised" in text and ws == 0
     text, ws, _ = plan(lib, S.config3_layer())
     assert text.startswith("conv_gemm_kernel tile=128x512") and ws == 0
+
+
+def test_tuning_hook_forces_and_clears_the_choice(lib):
+    """sparq_set_tuning: the documented keys change the plan, NULL restores the rules, junk is refused and changes nothing."""
+    conv = S.ConvLayer("conv3x3", 64, 32, 32, 512, 512, 3, 3, (1, 1), (1, 1), 0.5, S.Mode(4, S.OPT5, 1, 1))
+    lib.sparq_set_tuning.argtypes = [ctypes.c_char_p]
+    base = plan(lib, conv)[0]
+    try:
+        assert lib.sparq_set_tuning(b"path=gather,tile=128x256") == 0
+        assert plan(lib, conv)[0].startswith("conv_gemm_kernel tile=128x256")
+        assert lib.sparq_set_tuning(b"path=patch,patch_tn=64,patch_ws=0") == 0
+        text = plan(lib, conv)[0]
+        assert text.startswith("conv_patch_kernel tile=128x64") and "wave_specialised" not in text
+        for junk in (b"path=fast", b"tile=64x64", b"patch_tn=100", b"patch_ws=2", b"colour=red", b"path", b","):
+            assert lib.sparq_set_tuning(junk) == 1
+        assert plan(lib, conv)[0] == text                            # a refused spec leaves the override as it was
+    finally:
+        assert lib.sparq_set_tuning(None) == 0
+    assert plan(lib, conv)[0] == base
 
 
 def test_plan_rejects_bad_arguments(lib):
