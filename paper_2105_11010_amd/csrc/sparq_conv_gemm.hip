@@ -31,13 +31,14 @@ struct TileEntry { const char* name; int tm, tn; TileLauncher fn; };
 const TileEntry kTiles[] = {
     {"128x128", 128, 128, launch_tile_128x128_w2x2_a1b2},
     {"128x256", 128, 256, launch_tile_128x256_w1x4_a2b3},
-    {"128x512", 128, 512, launch_tile_128x512_w1x4_a1b3},
+    {"128x512", 128, 512, launch_tile_128x512_w1x4_half},
 };
 
 // Tile choice: the widest output-channel tile the layer fills, so that an activation
 // is gathered and trimmed as few times as possible; the tuning hook forces one.
-// A tile shape is usable only if all its weight loads stay inside the padded buffer.
-bool tile_fits(int tn, const ConvGeom& g) { return round_up(g.N, tn) <= g.Np; }
+// A tile shape is usable only if all its weight loads stay inside the padded buffer; the 512-wide tile's
+// main loop also needs every 64-byte reduction step to lie inside one filter tap (more than 32 channels).
+bool tile_fits(int tn, const ConvGeom& g) { return round_up(g.N, tn) <= g.Np && (tn != 512 || g.Cq % kStepK == 0); }
 
 // byte_output: the requantised uint8 output, which the 128x512 tile does not have.
 TileLauncher pick_tile(const ConvGeom& g, const Tuning& tune, bool byte_output = false) {

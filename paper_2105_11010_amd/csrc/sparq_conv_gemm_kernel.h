@@ -55,8 +55,15 @@ constexpr int lcm3(int a, int b, int c) { int l = a / gcd2(a, b) * b; return l /
 // Tile shape: TM output pixels x TN output channels per workgroup, WGM x WGN
 // wavefronts.  PA / PB: how many reduction steps ahead of their consumption the
 // activation / weight loads are issued.
-template <int TM, int TN, int WGM, int WGN, int PA, int PB, bool SPLIT = false, int WPC = 0>
+//
+// HALF selects the main loop pipelined by half steps (32 reduction indices): operand fragments are double-buffered
+// per half rather than per step, which halves their registers and leaves room for activation requests several
+// steps ahead even when a wavefront's accumulators fill the whole accumulation register file (128 x 128 results).
+// There PA counts the steps between an activation's request and its trim (the ring holds PA + 1 steps) and PB the
+// halves a weight fragment is requested ahead.
+template <int TM, int TN, int WGM, int WGN, int PA, int PB, bool SPLIT = false, int WPC = 0, bool HALF = false>
 struct TileCfg {
+    static constexpr bool kHalfPipe = HALF;
     static constexpr bool kSplitTrim = SPLIT;                   // trim half of the activations in each scheduling region
     static constexpr int kTM = TM, kTN = TN, kWGM = WGM, kWGN = WGN, kPA = PA, kPB = PB;
     static constexpr int kThreads = 64 * WGM * WGN;
@@ -70,17 +77,18 @@ struct TileCfg {
     // chunk each, into four different planes) land on different banks.
     static constexpr int kPlaneA = TM * kChunk + 64;
     static constexpr int kLdsA = 4 * kPlaneA;                   // bytes per stage
-    static constexpr int kStages = 3;                           // written two steps ahead, read one step ahead
+    static constexpr int kStages = HALF ? 4 : 3;                // written two steps ahead, read one step ahead
     static constexpr int kLdsBytes = kStages * kLdsA;
-    static constexpr int kUnroll = lcm3(2, PA, PB);             // main-loop unroll: every ring index compile-time
+    static constexpr int kUnroll = HALF ? 4 : lcm3(2, PA, PB);  // main-loop unroll: every ring index compile-time
     // resident workgroups per CU the register budget is set for (0: two with small accumulators, else one)
     static constexpr int kWgPerCu = WPC ? WPC : ((kFM * kFN * 16 <= 64) ? 2 : 1);
     // the widest tile has no registers to spare for a third epilogue copy: no requantised-byte output
     static constexpr bool kByteOutput = kFM * kFN * 16 <= 128;
     static_assert(TM % (32 * WGM) == 0 && TN % (32 * WGN) == 0, "tile must split into 32x32 fragments");
     static_assert((TM * 4) % kThreads == 0, "activation loads must divide evenly");
-    static_assert(PA >= 1 && PA <= 4 && PB >= 1 && PB <= 4, "prefetch depth");
-    static_assert(kUnroll % 2 == 0 && kUnroll % PA == 0 && kUnroll % PB == 0, "unroll must cover all rings");
+    static_assert(PA >= 1 && PA <= 4 && PB >= 1 && PB <= 8, "prefetch depth");
+    static_assert(HALF || (kUnroll % 2 == 0 && kUnroll % PA == 0 && kUnroll % PB == 0), "unroll must cover all rings");
+    static_assert(!HALF || (PA == 3 && (PB == 2 || PB == 4 || PB == 8) && kAChunks % 2 == 0), "half-step loop: rings of four steps / PB halves");
 };
 
 template <class Cfg, int KIND>
@@ -132,7 +140,35 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
         // request out-of-range activations (returned as zeros) and re-read the last weight
         // step; they are staged but never multiplied.
         int a_step = 0;                          // next activation step to request
+        // (opaque, so that the address arithmetic of the first requests is not computed once for all tiles and
+        // then kept in registers the main loop has no room for)
+        asm volatile("" : "+s"(a_step));
+        // Half-step form: the host picks it only when a tap's extent is a multiple of the 64-byte step, so the
+        // tap of a step is the same for all lanes and is tracked in scalar registers, advanced by one step per
+        // request (the general form below decodes the reduction index per lane).
+        int s_c0 = 0, s_kh = 0, s_kw = 0;
         auto load_a = [&](v4u (&ar)[AC]) {
+            if constexpr (Cfg::kHalfPipe) {
+                const bool k_ok = a_step < nkb;
+                const int32_t tap_off = (s_kh * p.W + s_kw) * p.C + s_c0 + kc * kChunk;
+                const bool c_ok = s_c0 + kc * kChunk < p.C;          // false in a tap's channel padding
+#pragma unroll
+                for (int i = 0; i < AC; ++i) {
+                    const bool ok = k_ok & c_ok & ((unsigned)(row_iy[i] + s_kh) < (unsigned)p.H) &
+                                    ((unsigned)(row_ix[i] + s_kw) < (unsigned)p.W);
+                    const uint32_t off = ok ? (uint32_t)(row_base[i] + tap_off) : kInvalidOffset;
+                    ar[i] = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, (int)off, 0, 0);
+                }
+                s_c0 += kStepK;
+                const bool wrap_c = s_c0 >= p.Cq;
+                s_c0 = wrap_c ? 0 : s_c0;
+                s_kw += wrap_c;
+                const bool wrap_w = s_kw >= p.KW;
+                s_kw = wrap_w ? 0 : s_kw;
+                s_kh += wrap_w;
+                ++a_step;
+                return;
+            }
             // where this lane's 16 bytes sit in the (kh, kw, c) reduction index
             const int k = a_step * kStepK + kc * kChunk;
             int tap = (int)((float)k * p.rcp_c);
@@ -198,6 +234,94 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) c[i][j][v] = 0;
 
+        if constexpr (Cfg::kHalfPipe) {
+        // ---- main loop pipelined by half steps ----
+        // Step s: requested at step s-2-PA, trimmed and staged during step s-2 (one half of a lane's chunks in
+        // each half step), its fragments read one half ahead of the matrix instructions that use them.  Weights
+        // of half h are requested at half h-PB, right after the matrix instructions that read the same registers.
+        constexpr int RA = PA + 1, RB = PB;
+        static_assert(RA == 4, "ring indices below assume four activation steps in flight");
+        v4u a_reg[RA][AC];            // activation requests in flight: step s in slot s % 4
+        v4i b_frag[RB][FN];           // weight fragments: half h in slot h % RB
+        v4i a_frag[2][FM];            // activation fragments: half h in slot h % 2
+        const int nhalves = 2 * nkb;
+        int b_half = 0;
+        auto load_bh = [&](v4i (&br)[FN]) {
+#pragma unroll
+            for (int j = 0; j < FN; ++j) br[j] = *reinterpret_cast<const v4i*>(wsrc + j * 32 * kChunk);
+            ++b_half;
+            wsrc += (b_half < nhalves) ? w_half : 0;
+        };
+        auto frags = [&](int stage, int ks, v4i (&a)[FM]) {
+            const uint8_t* sa = lds + stage * Cfg::kLdsA + (2 * ks + lhi) * Cfg::kPlaneA + (wm * Cfg::kWTM + l32) * kChunk;
+#pragma unroll
+            for (int i = 0; i < FM; ++i) a[i] = *reinterpret_cast<const v4i*>(sa + i * 32 * kChunk);
+        };
+        auto multiply = [&](const v4i (&a)[FM], const v4i (&b)[FN]) {
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int i = 0; i < FM; ++i) c[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], c[i][j], 0, 0, 0);
+        };
+        {
+            load_a(a_reg[0]);
+            load_a(a_reg[1]);
+            load_a(a_reg[2]);
+            load_a(a_reg[3]);
+#pragma unroll
+            for (int h = 0; h < RB; ++h) load_bh(b_frag[h]);
+            store_a(0, a_reg[0], 0, AC);
+            load_a(a_reg[0]);                                          // step 4
+            store_a(1, a_reg[1], 0, AC);
+        }
+        // Every request so far (and any register the compiler parked in scratch memory and reloads here) completes
+        // before the loop, so that inside it the counts of outstanding loads are exact from the first step on.
+        __builtin_amdgcn_s_waitcnt(0x0F70);                            // vmcnt(0)
+        __syncthreads();
+        frags(0, 0, a_frag[0]);
+        auto step = [&](auto u_) {
+            constexpr int u = decltype(u_)::value;                     // step number modulo 4
+            constexpr int st2 = (u + 2) % 4;
+            // first half: fragments of this step's second half, request step +5, multiply, trim half of step +2
+            frags(u, 1, a_frag[1]);
+            load_a(a_reg[(u + 1) % 4]);
+            multiply(a_frag[0], b_frag[(2 * u) % RB]);
+            load_bh(b_frag[(2 * u) % RB]);
+            store_a(st2, a_reg[st2], 0, AC / 2);
+#pragma unroll
+            for (int k = 0; k < FM * FN; ++k) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, (150 + FM * FN - 1) / (FM * FN), 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            // second half: fragments of the next step's first half, multiply, trim the other half
+            frags((u + 1) % 4, 0, a_frag[0]);
+            multiply(a_frag[1], b_frag[(2 * u + 1) % RB]);
+            load_bh(b_frag[(2 * u + 1) % RB]);
+            store_a(st2, a_reg[st2], AC / 2, AC);
+#pragma unroll
+            for (int k = 0; k < FM * FN; ++k) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, (110 + FM * FN - 1) / (FM * FN), 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+        };
+        const int nfull = nkb / 4 * 4;
+        for (int kb0 = 0; kb0 < nfull; kb0 += 4) {
+            step(std::integral_constant<int, 0>{});
+            step(std::integral_constant<int, 1>{});
+            step(std::integral_constant<int, 2>{});
+            step(std::integral_constant<int, 3>{});
+        }
+        if (nfull < nkb) step(std::integral_constant<int, 0>{});
+        if (nfull + 1 < nkb) step(std::integral_constant<int, 1>{});
+        if (nfull + 2 < nkb) step(std::integral_constant<int, 2>{});
+        } else {
         v4u a_reg[PA][AC];            // activation loads in flight
         v4i b_reg[PB][2][FN];         // weight fragments in flight / in use
         v4i a_frag[2][2][FM];         // activation fragments: [current / next step][half][fragment]
@@ -290,6 +414,8 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
             if (nfull + u < nkb)
                 body(nfull + u, a_frag[u & 1], a_frag[(u & 1) ^ 1], a_reg[(u + 1 + PA) % PA], a_reg[(u + 2) % PA],
                      b_reg[u % PB]);
+
+        }   // main loop form
 
         // ---- epilogue: undo the -128 offset, store int32 and/or dequantised fp32 ----
         // Register v of fragment (i, j) is pixel 8*(v/4) + 4*lhi + v%4, channel l32: each store
@@ -424,6 +550,6 @@ typedef sparq_status (*TileLauncher)(TrimKind, const GemmParams&, hipStream_t);
 #define SPARQ_DECLARE_TILE(name) sparq_status name(TrimKind kind, const GemmParams& p, hipStream_t s)
 SPARQ_DECLARE_TILE(launch_tile_128x128_w2x2_a1b2);
 SPARQ_DECLARE_TILE(launch_tile_128x256_w1x4_a2b3);
-SPARQ_DECLARE_TILE(launch_tile_128x512_w1x4_a1b3);
+SPARQ_DECLARE_TILE(launch_tile_128x512_w1x4_half);
 
 }  // namespace sparq
