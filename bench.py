@@ -452,6 +452,37 @@ def main():
             del it2
             torch.cuda.empty_cache()
 
+        # the default layer from packed storage (n-bit data + ShiftCtrl + MuxCtrl records) and with 2:4 pruned weights;
+        # ops counted as the dense layer's 2*M*K*N in both cases (what the layer computes, zeros included)
+        L = dom["layer"]
+        pm = dom["m"]
+        if L.mode.window_bits < 8 and dom["out"] is not None:
+            nb = sq.sparq_packed_act_bytes(L.B * L.H * L.W, L.C, pm, 1)
+            px = torch.empty(nb, dtype=torch.uint8, device=dev)
+            sq.sparq_pack_act(dom["x"], px, pm, 1)
+            wsb = sq.sparq_conv_packed_workspace_bytes(dom["d"], pm)
+            ws = torch.empty(max(wsb, 1), dtype=torch.uint8, device=dev)
+            ms5 = time_calls(torch, lambda i: sq.sparq_conv_gemm_packed(px, 1, dom["packed"], dom["d"], pm, scale=dom["sc"],
+                                                                        out=dom["out"], workspace=ws), args.warmup, args.steps)
+            e = entry(wl_name + ", input held in packed storage (unpack pass + the same kernel at plain 8 bits)", [L], ms5, 4)
+            e["packed_input_bytes"] = nb
+            also.append(e)
+            del px, ws
+        if L.C % 4 == 0 and dom["out"] is not None:
+            wv, wi = S.gen_sparse24_weights(L.w_shape(), S.rng_for(cfg_id, 24))
+            wvd, wid = torch.from_numpy(wv).to(dev), torch.from_numpy(wi).to(dev)
+            sp = torch.empty(sq.sparq_sparse24_packed_bytes(dom["d"], pm), dtype=torch.uint8, device=dev)
+            sq.sparq_pack_weights_sparse24(wvd, wid, dom["d"], pm, sp)
+            ws = torch.empty(max(sq.sparq_sparse24_workspace_bytes(dom["d"], pm), 1), dtype=torch.uint8, device=dev)
+            ms6 = time_calls(torch, lambda i: sq.sparq_conv_gemm_sparse24(dom["x"], sp, dom["d"], pm, scale=dom["sc"], out=dom["out"],
+                                                                          workspace=ws), args.warmup, args.steps)
+            e = entry(wl_name + ", 2:4 pruned weights (activations picked by the kept weights, then paired; emulated on the "
+                                "dense matrix cores over an expanded problem)", [L], ms6, 4)
+            e["note"] = "value counts the dense layer's operations; the emulation multiplies 4x the channels when pairing is on"
+            also.append(e)
+            del wvd, wid, sp, ws
+        torch.cuda.empty_cache()
+
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload ----
     cpu = None
     if not args.no_cpu_baseline:

@@ -14,15 +14,15 @@
  * positive code on a rejected argument (1 = invalid argument).
  *
  * Readings of points the paper leaves open:
- *   - rounding "according to the residual LSBs" (Section 3.1) is round half
- *     up inside the chosen window;
+ *   - rounding by the residual low bits (Section 3.1) is round half up inside
+ *     the chosen window;
  *   - the window position is fixed by the leading one of the UNROUNDED value
  *     and a rounding carry out of the window saturates at 2^n - 1;
  *   - the dot-product vector of Eq. 1 is ordered (kh, kw, c) with the input
  *     channel c fastest, so a pair is two consecutive input channels of one
  *     pixel; an odd last channel has an implicit zero partner;
  *   - for n < 4 a value whose partner is zero gets a 2n-bit window (Section
- *     5.1, "total window sizes are 6 and 4 bits") whose allowed shifts are the
+ *     5.1: total window sizes of 6 and 4 bits) whose allowed shifts are the
  *     t for which both t and t+n are allowed n-bit shifts (the two n-bit
  *     multipliers of Eq. 4 acting as the high and low half);
  *   - requantisation rounds to nearest with ties to even, product and
@@ -93,9 +93,9 @@ int sparq_requant_ref(const int32_t *acc, const float *factor, uint8_t *y,
 /* ---- 2:4 structured weight sparsity (Section 4, sparse tensor core; Section 5.3) ----------------------------
  * Of every four adjacent weights along the input channels two are kept, stored with their coordinates:
  * w_vals [N][KH][KW][C/2] int8 and w_idx [N][KH][KW][C/2], entries 2g and 2g+1 of a tap holding the positions
- * (0..3, ascending, distinct) of the kept weights of group g (channels 4g .. 4g+3).  "The stored coordinates
- * indicate which activations are picked"; "then vSPARQ comes into play, inspecting pairs of activations": the
- * two activations an output channel picks from a group form its vSPARQ pair (a reading: the figure that shows
+ * (0..3, ascending, distinct) of the kept weights of group g (channels 4g .. 4g+3).  The coordinates select the
+ * activations that are multiplied, and vSPARQ then looks at pairs of the selected activations: the two
+ * activations an output channel picks from a group form its vSPARQ pair (a reading: the figure that shows
  * the pairing is not available), so the trim of an activation depends on the output channel's coordinates.
  *   acc[m][n] = sum over taps, groups g of  ta * w_vals[..2g] + tb * w_vals[..2g+1],
  *   (ta, tb) = the pair rule of Eq. 2 on (x[..4g + idx0], x[..4g + idx1])   (each trimmed alone if vSPARQ is off).
