@@ -283,6 +283,40 @@ def machine_probes(torch, dev):
                     "data: the chip lowers its clock under the power the multipliers draw); copy: 1 GiB read + 1 GiB written"}
 
 
+def sclk_during(torch, fn, seconds=1.5):
+    """Median shader clock (MHz, as `rocm-smi --showclocks` reports it from a child process) while fn() is launched
+    back to back for `seconds`; None if the tool gives no reading.  Shows the chip lowering its clock under load."""
+    import re
+    import statistics
+    import subprocess
+    import threading
+    readings, stop = [], threading.Event()
+
+    def sampler():
+        while not stop.is_set():
+            try:
+                text = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=5).stdout
+                m = re.search(r"sclk clock level: \S+ \((\d+)Mhz\)", text)
+                if m:
+                    readings.append((time.time(), int(m.group(1))))
+            except (OSError, subprocess.SubprocessError):
+                return
+            stop.wait(0.1)
+
+    th = threading.Thread(target=sampler, daemon=True)
+    t0 = time.time()
+    th.start()
+    while time.time() - t0 < seconds:
+        for _ in range(100):
+            fn()
+        torch.cuda.synchronize()
+    t1 = time.time()
+    stop.set()
+    th.join(timeout=6)
+    vals = [v for t, v in readings if t0 + 0.4 <= t <= t1]
+    return int(statistics.median(vals)) if vals else None
+
+
 def streaming_kernels(sq, S, torch, dev, dom, reps):
     """Standalone trim and dequantisation kernels, HBM-bound.  'cold': on config 3's materialised A (302 MB in, 302 MB
     out per call) / on three rotating 134 MB accumulator tensors -- more than the 256 MB last-level cache holds, so every
@@ -405,6 +439,13 @@ def main():
         z_ms = time_calls(torch, lambda i: run_layer(sq, zero_it, args.output), max(2, args.warmup), reps)
         roofline["same_kernel_zero_operands"] = {"TOPS": round(L.ops / z_ms / 1e9, 2), "frac": round(L.ops / z_ms / 1e9 / PEAK_INT8_TOPS, 4),
                                                  "ms_per_launch": round(z_ms, 4)}
+        # the shader clock the chip settles at while each of the two runs back to back (2400 MHz nominal)
+        roofline["sclk_mhz"] = {"nominal": 2400, "kernel_on_the_workload": sclk_during(torch, lambda: run_layer(sq, dom, args.output)),
+                                "same_kernel_zero_operands": sclk_during(torch, lambda: run_layer(sq, zero_it, args.output)),
+                                "source": "rocm-smi --showclocks, median over 1.5 s of back-to-back launches"}
+        if roofline["sclk_mhz"]["kernel_on_the_workload"]:
+            # the published peak is 5.0 POP/s at 2400 MHz; at the clock the chip grants this kernel it is proportionally less
+            roofline["frac_of_peak_at_the_measured_clock"] = round(dom_tops / (PEAK_INT8_TOPS * roofline["sclk_mhz"]["kernel_on_the_workload"] / 2400.0), 4)
         del xz, wz, pz, zero_it
 
     # ---- standalone trim and dequant kernels (HBM-bound) ----
