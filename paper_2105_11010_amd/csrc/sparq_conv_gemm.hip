@@ -29,7 +29,7 @@ Tuning current_tuning() {
 
 struct TileEntry { const char* name; int tm, tn; TileLauncher fn; };
 const TileEntry kTiles[] = {
-    {"128x128", 128, 128, launch_tile_128x128_w2x2_a1b2},
+    {"128x128", 128, 128, launch_tile_128x128_w2x2_a4b2},
     {"128x256", 128, 256, launch_tile_128x256_w1x4_a2b3},
     {"128x512", 128, 512, launch_tile_128x512_w1x4_half},
 };

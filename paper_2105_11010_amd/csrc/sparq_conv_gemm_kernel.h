@@ -548,7 +548,7 @@ sparq_status launch_kind(TrimKind kind, const GemmParams& p, hipStream_t s) {
 // kernel for every trim variant and exports a launcher with this signature.
 typedef sparq_status (*TileLauncher)(TrimKind, const GemmParams&, hipStream_t);
 #define SPARQ_DECLARE_TILE(name) sparq_status name(TrimKind kind, const GemmParams& p, hipStream_t s)
-SPARQ_DECLARE_TILE(launch_tile_128x128_w2x2_a1b2);
+SPARQ_DECLARE_TILE(launch_tile_128x128_w2x2_a4b2);
 SPARQ_DECLARE_TILE(launch_tile_128x256_w1x4_a2b3);
 SPARQ_DECLARE_TILE(launch_tile_128x512_w1x4_half);
 
