@@ -151,9 +151,15 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
         const int pix = my_pix + i * (NT / PL);
         const int ch = l_cb * Cfg::kCB + my_c;
         // only the staging wavefronts of the wave-specialised form handle the pixel remap of strided 1x1 layers
-        uint32_t off = patch_pixel_offset_u32<WS>(g, lt, pix, p.C, kPatchInvalidOffset);
-        off = (ch < p.C) ? off : kPatchInvalidOffset;            // a tap's channel padding reads as zero
-        off += (off != kPatchInvalidOffset) ? (uint32_t)ch : 0u;
+        uint32_t off = kPatchInvalidOffset;
+        // The staging wavefronts' own loop can afford a uniform branch around the address arithmetic of a chunk that
+        // lies past the patch altogether; the request itself stays unconditional (it then reads 0 without touching
+        // memory), so that the counts of outstanding requests stay exact.
+        if (!WS || i * (NT / PL) < lt.npix) {
+            off = patch_pixel_offset_u32<WS>(g, lt, pix, p.C, kPatchInvalidOffset);
+            off = (ch < p.C) ? off : kPatchInvalidOffset;            // a tap's channel padding reads as zero
+            off += (off != kPatchInvalidOffset) ? (uint32_t)ch : 0u;
+        }
         a_reg[i] = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, (int)off, 0, 0);   // out of range reads 0
     };
     // trim + flip to signed + write into the patch buffer at `buf`
@@ -278,8 +284,10 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
                 uint8_t* sbuf = lds + (p_buf ^ 1) * buf_bytes;
 #pragma unroll
                 for (int i = 0; i < AC; ++i) {    // trim and write the next unit's chunks, request those of the unit after it
-                    stage_chunk(i, sbuf);
-                    load_chunk(i);
+                    // (a chunk whose 256 / PL pixels all lie past the patch holds nothing: skip its trim -- the
+                    // staging capacity is sized for the layer's largest patch, most tiles' patches are smaller)
+                    if (i * (NT / PL) < stage_npix) stage_chunk(i, sbuf);
+                    load_chunk(i);                // unconditional: a request under a condition costs exact wait counts
                 }
                 p_buf ^= 1;
                 const bool tile_done = p_cb == p.ncb - 1;
