@@ -147,19 +147,26 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
             load_tile_patch();
         }
     };
+    uint32_t pix_off[AC];                         // staging wavefronts: byte offset of the pixel of chunk i, kept per tile
     auto load_chunk = [&](int i) __attribute__((always_inline)) {
         const int pix = my_pix + i * (NT / PL);
         const int ch = l_cb * Cfg::kCB + my_c;
-        // only the staging wavefronts of the wave-specialised form handle the pixel remap of strided 1x1 layers
-        uint32_t off = kPatchInvalidOffset;
-        // The staging wavefronts' own loop can afford a uniform branch around the address arithmetic of a chunk that
-        // lies past the patch altogether; the request itself stays unconditional (it then reads 0 without touching
-        // memory), so that the counts of outstanding requests stay exact.
-        if (!WS || i * (NT / PL) < lt.npix) {
+        uint32_t off;
+        if constexpr (WS) {
+            // The staging wavefronts' own loop can afford uniform branches around address arithmetic: a pixel's offset
+            // is computed for the first channel block of a tile and reused for the others, and not at all for a chunk
+            // that lies past the patch altogether.  The request itself stays unconditional (it then reads 0 without
+            // touching memory), so that the counts of outstanding requests stay exact.
+            // (only these wavefronts handle the pixel remap of strided 1x1 layers)
+            if (l_cb == 0)
+                pix_off[i] = (i * (NT / PL) < lt.npix) ? patch_pixel_offset_u32<WS>(g, lt, pix, p.C, kPatchInvalidOffset)
+                                                       : kPatchInvalidOffset;
+            off = pix_off[i];
+        } else {
             off = patch_pixel_offset_u32<WS>(g, lt, pix, p.C, kPatchInvalidOffset);
-            off = (ch < p.C) ? off : kPatchInvalidOffset;            // a tap's channel padding reads as zero
-            off += (off != kPatchInvalidOffset) ? (uint32_t)ch : 0u;
         }
+        off = (ch < p.C) ? off : kPatchInvalidOffset;            // a tap's channel padding reads as zero
+        off += (off != kPatchInvalidOffset) ? (uint32_t)ch : 0u;
         a_reg[i] = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, (int)off, 0, 0);   // out of range reads 0
     };
     // trim + flip to signed + write into the patch buffer at `buf`
