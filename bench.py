@@ -283,37 +283,44 @@ def machine_probes(torch, dev):
                     "data: the chip lowers its clock under the power the multipliers draw); copy: 1 GiB read + 1 GiB written"}
 
 
+def sclk_file(torch):
+    """The sysfs file with the shader-clock levels of device 0 (the current one is starred), or None."""
+    import glob
+    files = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))
+    if len(files) > 1:
+        # several cards in sysfs: take the one at the PCI address of the device the benchmark runs on
+        p = torch.cuda.get_device_properties(0)
+        want = "%04x:%02x:%02x" % (getattr(p, "pci_domain_id", 0), getattr(p, "pci_bus_id", -1), getattr(p, "pci_device_id", 0))
+        for f in files:
+            try:
+                if want in open(os.path.join(os.path.dirname(f), "uevent")).read().lower():
+                    return f
+            except OSError:
+                pass
+        return None
+    return files[0] if files else None
+
+
 def sclk_during(torch, fn, seconds=1.5):
-    """Median shader clock (MHz, as `rocm-smi --showclocks` reports it from a child process) while fn() is launched
-    back to back for `seconds`; None if the tool gives no reading.  Shows the chip lowering its clock under load."""
+    """Median shader clock (MHz; the starred level of sysfs pp_dpm_sclk, the file rocm-smi prints) while fn() is
+    launched back to back for `seconds`; None if there is no reading.  Plain file reads between batches of launches:
+    no child process.  Shows the chip lowering its clock under load."""
     import re
     import statistics
-    import subprocess
-    import threading
-    readings, stop = [], threading.Event()
-
-    def sampler():
-        while not stop.is_set():
-            try:
-                text = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=5).stdout
-                m = re.search(r"sclk clock level: \S+ \((\d+)Mhz\)", text)
-                if m:
-                    readings.append((time.time(), int(m.group(1))))
-            except (OSError, subprocess.SubprocessError):
-                return
-            stop.wait(0.1)
-
-    th = threading.Thread(target=sampler, daemon=True)
-    t0 = time.time()
-    th.start()
+    path = sclk_file(torch)
+    if path is None:
+        return None
+    vals, t0 = [], time.time()
     while time.time() - t0 < seconds:
         for _ in range(100):
             fn()
+        try:
+            m = re.search(r"(\d+)Mhz \*", open(path).read())
+        except OSError:
+            return None
+        if m and time.time() - t0 > 0.4:
+            vals.append(int(m.group(1)))
         torch.cuda.synchronize()
-    t1 = time.time()
-    stop.set()
-    th.join(timeout=6)
-    vals = [v for t, v in readings if t0 + 0.4 <= t <= t1]
     return int(statistics.median(vals)) if vals else None
 
 
@@ -442,7 +449,7 @@ def main():
         # the shader clock the chip settles at while each of the two runs back to back (2400 MHz nominal)
         roofline["sclk_mhz"] = {"nominal": 2400, "kernel_on_the_workload": sclk_during(torch, lambda: run_layer(sq, dom, args.output)),
                                 "same_kernel_zero_operands": sclk_during(torch, lambda: run_layer(sq, zero_it, args.output)),
-                                "source": "rocm-smi --showclocks, median over 1.5 s of back-to-back launches"}
+                                "source": "sysfs pp_dpm_sclk (what rocm-smi --showclocks prints), median over 1.5 s of back-to-back launches"}
         if roofline["sclk_mhz"]["kernel_on_the_workload"]:
             # the published peak is 5.0 POP/s at 2400 MHz; at the clock the chip grants this kernel it is proportionally less
             roofline["frac_of_peak_at_the_measured_clock"] = round(dom_tops / (PEAK_INT8_TOPS * roofline["sclk_mhz"]["kernel_on_the_workload"] / 2400.0), 4)
