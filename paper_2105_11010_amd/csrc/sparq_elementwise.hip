@@ -8,6 +8,11 @@
 namespace sparq {
 
 constexpr int kEwThreads = 256;
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+typedef int v4s __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+// bytes read + written from which a streaming kernel takes the non-temporal form: the last-level cache holds 256 MiB
+constexpr int64_t kStreamedBytes = (int64_t)256 << 20;
 
 static int ew_grid(int64_t work_items, int per_block) {
     int64_t blocks = (work_items + per_block - 1) / per_block;
@@ -20,17 +25,21 @@ static int ew_grid(int64_t work_items, int per_block) {
 // ---- standalone trim ---------------------------------------------------------
 // Even C: pairs (2j, 2j+1) of a row are also pairs of the flattened array, so
 // the tensor is processed as one stream of 16-byte words.
-template <int KIND>
+// NT: non-temporal loads and stores, for tensors larger than the last-level cache that are streamed once (+8 % there;
+// cache-resident or in-place tensors are faster with ordinary accesses).
+template <int KIND, bool NT>
 __global__ __launch_bounds__(kEwThreads) void trim_vec_kernel(const uint4* x, uint4* y,
                                                               int64_t n_vec, TrimLuts L) {
     const int64_t stride = (int64_t)gridDim.x * kEwThreads;
     for (int64_t i = (int64_t)blockIdx.x * kEwThreads + threadIdx.x; i < n_vec; i += stride) {
-        uint4 v = x[i];
+        const v4u* src = reinterpret_cast<const v4u*>(x) + i;
+        v4u v = NT ? __builtin_nontemporal_load(src) : *src;
         v.x = trim4_kind<KIND>(v.x, L);
         v.y = trim4_kind<KIND>(v.y, L);
         v.z = trim4_kind<KIND>(v.z, L);
         v.w = trim4_kind<KIND>(v.w, L);
-        y[i] = v;
+        if (NT) __builtin_nontemporal_store(v, reinterpret_cast<v4u*>(y) + i);
+        else reinterpret_cast<v4u*>(y)[i] = v;
     }
 }
 
@@ -69,8 +78,12 @@ static void launch_trim_kind(const uint8_t* x, uint8_t* y, int64_t rows, int C, 
     int64_t done = 0;
     if (vec_ok && bytes >= 16) {
         const int64_t n_vec = bytes / 16;
-        trim_vec_kernel<KIND><<<ew_grid(n_vec, kEwThreads * 4), kEwThreads, 0, s>>>(
-            reinterpret_cast<const uint4*>(x), reinterpret_cast<uint4*>(y), n_vec, L);
+        if (x != y && 2 * bytes >= kStreamedBytes)
+            trim_vec_kernel<KIND, true><<<ew_grid(n_vec, kEwThreads * 4), kEwThreads, 0, s>>>(
+                reinterpret_cast<const uint4*>(x), reinterpret_cast<uint4*>(y), n_vec, L);
+        else
+            trim_vec_kernel<KIND, false><<<ew_grid(n_vec, kEwThreads * 4), kEwThreads, 0, s>>>(
+                reinterpret_cast<const uint4*>(x), reinterpret_cast<uint4*>(y), n_vec, L);
         done = n_vec * 16;
     }
     if (done < bytes) {
@@ -126,20 +139,23 @@ sparq_status launch_trim_pad(const uint8_t* x, uint8_t* xp, int64_t pixels, int 
 }
 
 // ---- dequantisation ----------------------------------------------------------
+template <bool NT>
 __global__ __launch_bounds__(kEwThreads) void dequant_vec_kernel(const int4* __restrict__ acc, const float* __restrict__ scale,
                                                                  float4* __restrict__ out, int64_t n_vec, int N) {
     // N % 4 == 0: a 16-byte word never straddles a row
     const int64_t stride = (int64_t)gridDim.x * kEwThreads;
     for (int64_t i = (int64_t)blockIdx.x * kEwThreads + threadIdx.x; i < n_vec; i += stride) {
         const int n = (int)((i * 4) % N);
-        const int4 a = acc[i];
+        const v4s* src = reinterpret_cast<const v4s*>(acc) + i;
+        const v4s a = NT ? __builtin_nontemporal_load(src) : *src;
         const float4 s = *reinterpret_cast<const float4*>(scale + n);
-        float4 o;
+        v4f o;
         o.x = __fmul_rn((float)a.x, s.x);
         o.y = __fmul_rn((float)a.y, s.y);
         o.z = __fmul_rn((float)a.z, s.z);
         o.w = __fmul_rn((float)a.w, s.w);
-        out[i] = o;
+        if (NT) __builtin_nontemporal_store(o, reinterpret_cast<v4f*>(out) + i);
+        else reinterpret_cast<v4f*>(out)[i] = o;
     }
 }
 
@@ -272,8 +288,12 @@ extern "C" sparq_status sparq_dequant(const int32_t* acc, const float* scale, fl
     const int64_t total = M * N;
     if (N % 4 == 0 && aligned(acc, 16) && aligned(out, 16) && aligned(scale, 16)) {
         const int64_t n_vec = total / 4;
-        dequant_vec_kernel<<<ew_grid(n_vec, kEwThreads * 4), kEwThreads, 0, s>>>(
-            reinterpret_cast<const int4*>(acc), scale, reinterpret_cast<float4*>(out), n_vec, N);
+        if (8 * total >= kStreamedBytes)
+            dequant_vec_kernel<true><<<ew_grid(n_vec, kEwThreads * 4), kEwThreads, 0, s>>>(
+                reinterpret_cast<const int4*>(acc), scale, reinterpret_cast<float4*>(out), n_vec, N);
+        else
+            dequant_vec_kernel<false><<<ew_grid(n_vec, kEwThreads * 4), kEwThreads, 0, s>>>(
+                reinterpret_cast<const int4*>(acc), scale, reinterpret_cast<float4*>(out), n_vec, N);
     } else {
         dequant_scalar_kernel<<<ew_grid(total, kEwThreads * 4), kEwThreads, 0, s>>>(acc, scale, out, total, N);
     }
