@@ -454,9 +454,9 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
                             const int row_bytes = (i * 32 + 8 * (v / 4) + (v % 4)) * pitch;
                             const int32_t r = c[i][j][v] + corr;
                             const int off = (int)(lane_off + (uint32_t)row_bytes);
-                            if constexpr (kAcc) __builtin_amdgcn_raw_buffer_store_b32(r, arsrc, off, 0, 0);
+                            if constexpr (kAcc) __builtin_amdgcn_raw_buffer_store_b32(r, arsrc, off, 0, kResultStorePolicy);
                             if constexpr (kOut)
-                                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, __fmul_rn((float)r, sc)), orsrc, off, 0, 0);
+                                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, __fmul_rn((float)r, sc)), orsrc, off, 0, kResultStorePolicy);
                             if constexpr (kU8)
                                 __builtin_amdgcn_raw_buffer_store_b8((unsigned char)requant_u8(r, sc), orsrc, off, 0, 0);
                         }

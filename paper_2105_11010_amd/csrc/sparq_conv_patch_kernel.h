@@ -470,9 +470,9 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
                             for (int j = 0; j < FN; ++j) {
                                 const int32_t r = c[i][j][v] + corr[j];
                                 const int off = (int)(lane_off[j] + (uint32_t)row_bytes);
-                                if constexpr (kAcc) __builtin_amdgcn_raw_buffer_store_b32(r, arsrc, off, 0, 0);
+                                if constexpr (kAcc) __builtin_amdgcn_raw_buffer_store_b32(r, arsrc, off, 0, kResultStorePolicy);
                                 if constexpr (kOut)
-                                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, __fmul_rn((float)r, sc[j])), orsrc, off, 0, 0);
+                                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, __fmul_rn((float)r, sc[j])), orsrc, off, 0, kResultStorePolicy);
                                 if constexpr (kU8)
                                     __builtin_amdgcn_raw_buffer_store_b8((unsigned char)requant_u8(r, sc[j]), orsrc, off, 0, 0);
                             }
