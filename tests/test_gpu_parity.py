@@ -91,12 +91,38 @@ def test_trim_in_place_large_and_empty(sq, oracle):
     sq.sparq_trim(e, e, sq.mode(*mode.astuple()))
 
 
+def test_trim_streamed_form(sq, oracle):
+    """A call that moves 256 MiB or more out of place takes the kernel with non-temporal accesses: every byte
+    against the oracle on a 136 MB tensor with a ragged tail (one 16-byte word plus a few pairs left over)."""
+    mode = S.Mode(4, S.OPT3, 1, 1)
+    block = S.gen_activations((1 << 22,), 0.5, S.rng_for(8, 210))
+    x = np.resize(block, (1, (136 << 20) + 22))
+    xd, yd = dev(x), torch.zeros(x.shape, dtype=torch.uint8, device="cuda:0")
+    sq.sparq_trim(xd, yd, sq.mode(*mode.astuple()))
+    torch.cuda.synchronize()
+    assert np.array_equal(yd.cpu().numpy(), oracle.trim(x, **mode.kwargs()))
+
+
 # ------------------------------------------------------------- dequant ------
 
 @pytest.mark.parametrize("M,N", [(1, 1), (37, 19), (513, 64), (1000, 160)])
 def test_dequant(sq, oracle, M, N):
     rng = S.rng_for(8, 300 + N)
     acc = rng.integers(-2 ** 31, 2 ** 31, size=(M, N), dtype=np.int64).astype(np.int32)
+    sc = S.gen_scales(N, rng)
+    out = torch.empty((M, N), dtype=torch.float32, device="cuda:0")
+    sq.sparq_dequant(dev(acc), dev(sc), out)
+    torch.cuda.synchronize()
+    ref = oracle.dequant(acc, sc)
+    err = np.abs(out.cpu().numpy().astype(np.float64) - ref)
+    assert np.all(err <= 1e-6 * np.abs(ref))
+
+
+def test_dequant_streamed_form(sq, oracle):
+    """8 * M * N >= 256 MiB: the dequantisation kernel with non-temporal accesses, every element."""
+    M, N = 65537, 512
+    rng = S.rng_for(8, 310)
+    acc = np.resize(rng.integers(-2 ** 31, 2 ** 31, size=(1 << 20,), dtype=np.int64).astype(np.int32), (M, N))
     sc = S.gen_scales(N, rng)
     out = torch.empty((M, N), dtype=torch.float32, device="cuda:0")
     sq.sparq_dequant(dev(acc), dev(sc), out)
