@@ -85,6 +85,21 @@ def test_tuning_hook_forces_and_clears_the_choice(lib):
     assert plan(lib, conv)[0] == base
 
 
+def test_widest_gather_tile_only_with_step_aligned_taps(lib):
+    """The 128 x 512 tile tracks a step's filter tap in scalar registers, so every 64-byte reduction step must lie
+    inside one tap (more than 32 channels); otherwise, and when 512 columns would read past the padded weights, the
+    library takes the next tile, also when the hook asks for the widest one."""
+    lib.sparq_set_tuning.argtypes = [ctypes.c_char_p]
+    mode = S.Mode(4, S.OPT5, 1, 1)
+    try:
+        assert lib.sparq_set_tuning(b"path=gather,tile=128x512") == 0
+        assert plan(lib, S.ConvLayer("c64", 1, 9, 9, 64, 300, 3, 3, (1, 1), (1, 1)), mode)[0].startswith("conv_gemm_kernel tile=128x512")
+        assert plan(lib, S.ConvLayer("c32", 1, 9, 9, 32, 300, 3, 3, (1, 1), (1, 1)), mode)[0].startswith("conv_gemm_kernel tile=128x256")
+        assert plan(lib, S.ConvLayer("n520", 1, 9, 9, 64, 520, 3, 3, (1, 1), (1, 1)), mode)[0].startswith("conv_gemm_kernel tile=128x256")
+    finally:
+        assert lib.sparq_set_tuning(None) == 0
+
+
 def test_plan_rejects_bad_arguments(lib):
     buf = ctypes.create_string_buffer(64)
     m = Mode(4, 0x1F, 1, 1)
