@@ -190,9 +190,24 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
     int c_tile = (int)blockIdx.x, c_cb = 0, c_tm = 0, c_tn = 0;
     int c_pwt16 = 0;                              // bytes per patch row inside a plane
     int32_t fbase[FM];                            // patch byte offset of this lane's pixel (tap 0,0) per fragment
+    // Per-channel constants of the tile's epilogue (128 * sum_k w[n][k] and the dequantisation / requantisation
+    // factor), requested when the tile starts: at its end they have long arrived, where a request placed there
+    // exposed a memory latency per tile -- a fifth of the time of layers with one reduction step per tile.
+    int32_t corr[FN];
+    float sc[FN];
+    const float* scale_or_dummy = (p.out || p.out_u8) ? p.scale : reinterpret_cast<const float*>(p.colsum);
     auto setup_compute_tile = [&]() __attribute__((always_inline)) {
         c_tm = c_tile / p.tiles_n;
         c_tn = c_tile - c_tm * p.tiles_n;
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+            const int n = c_tn * TN + wn * Cfg::kWTN + j * 32 + l32;
+            const int nc = n < p.N ? n : 0;
+            // both constants are loaded on every path (a load under a condition makes the compiler put a full
+            // memory wait in front of every store of the epilogue)
+            corr[j] = p.colsum[nc] * 128;
+            sc[j] = scale_or_dummy[nc];
+        }
         const TilePatch t = tile_patch(g, c_tm * kPatchTM);
         c_pwt16 = t.pwt * kChunk;
 #pragma unroll
@@ -424,27 +439,14 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
             // instruction writes two full 128-byte runs of consecutive channels.
             const int64_t m0 = (int64_t)c_tm * kPatchTM;
             const int n0 = c_tn * TN;
-            constexpr int corr_mul = 128;
-            const float* scale_or_dummy = (p.out || p.out_u8) ? p.scale : reinterpret_cast<const float*>(p.colsum);
             {
                 // Buffer stores relative to the tile's first row: the lane's part of the offset is computed
                 // once, every row adds a uniform multiple of the row pitch, and rows past M or channels
                 // past N fall outside the buffer's range and are dropped by the hardware (no per-row
                 // branches, no 64-bit address arithmetic).  One copy per combination of outputs, chosen per tile.
                 const int rows = g.M - (int)m0 < kPatchTM ? g.M - (int)m0 : kPatchTM;
-                int32_t corr[FN];
-                float sc[FN];
 #pragma unroll
-                for (int j = 0; j < FN; ++j) {
-                    const int n = n0 + wn * Cfg::kWTN + j * 32 + l32;
-                    const int nc = n < p.N ? n : 0;
-                    // both per-channel constants are loaded on every path (a load under a condition makes
-                    // the compiler put a full memory wait in front of every store below)
-                    corr[j] = p.colsum[nc] * corr_mul;
-                    sc[j] = scale_or_dummy[nc];
-                }
-#pragma unroll
-                for (int j = 0; j < FN; ++j) asm volatile("" : "+v"(corr[j]), "+v"(sc[j]));   // loads have landed from here on
+                for (int j = 0; j < FN; ++j) asm volatile("" : "+v"(corr[j]), "+v"(sc[j]));   // the tile's constants have landed from here on
                 auto store_tile = [&](auto acc_, auto out_, auto u8_) __attribute__((always_inline)) {
                     constexpr bool kAcc = decltype(acc_)::value, kOut = decltype(out_)::value, kU8 = decltype(u8_)::value;
                     constexpr int kElem = kU8 ? 1 : 4;                 // bytes per stored result
