@@ -135,6 +135,23 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
             row_base[i] = (int32_t)((((int64_t)b * p.H + iy0) * p.W + ix0) * p.C);
         }
 
+        // Per-channel constants of the epilogue (128 * sum_k w[n][k] and the dequantisation / requantisation factor),
+        // requested when the tile starts where the registers allow it: a request at the tile's end exposes a memory
+        // latency per tile, which short reductions (a network's first layer: six steps) cannot afford.
+        constexpr bool kEarlyConsts = FM * FN * 16 <= 128;
+        int32_t corr_t[FN];
+        float sc_t[FN];
+        if constexpr (kEarlyConsts) {
+            const bool scaled = p.out || p.out_u8;
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                const int n = n0 + wn * Cfg::kWTN + j * 32 + l32;
+                const int nc = n < p.N ? n : 0;
+                corr_t[j] = 128 * p.colsum[nc];
+                sc_t[j] = scaled ? p.scale[nc % p.scale_n] : 0.0f;
+            }
+        }
+
         // Everything inside the main loop is branch-free so that the loop body stays one
         // basic block and outstanding loads can be waited on exactly.  Steps past the end
         // request out-of-range activations (returned as zeros) and re-read the last weight
@@ -443,8 +460,15 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
                     const int nc = n < p.N ? n : 0;
                     // both constants are loaded on every path (a load under a condition makes the
                     // compiler put a full memory wait in front of every store below)
-                    int32_t corr = 128 * p.colsum[nc];
-                    float sc = scale_or_dummy[(kOut || kU8) ? nc % p.scale_n : nc];
+                    int32_t corr;
+                    float sc;
+                    if constexpr (kEarlyConsts) {
+                        corr = corr_t[j];
+                        sc = sc_t[j];
+                    } else {
+                        corr = 128 * p.colsum[nc];
+                        sc = scale_or_dummy[(kOut || kU8) ? nc % p.scale_n : nc];
+                    }
                     const uint32_t lane_off = n < p.N ? (uint32_t)((wm * Cfg::kWTM + 4 * lhi) * pitch + n * kElem) : kInvalidOffset;
                     asm volatile("" : "+v"(corr), "+v"(sc));
 #pragma unroll
@@ -475,8 +499,15 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
                 for (int j = 0; j < FN; ++j) {
                     const int n = n0 + wn * Cfg::kWTN + j * 32 + l32;
                     const int nc = n < p.N ? n : 0;
-                    int32_t corr = 128 * p.colsum[nc];
-                    float sc = p.scale[nc % p.scale_n];
+                    int32_t corr;
+                    float sc;
+                    if constexpr (kEarlyConsts) {
+                        corr = corr_t[j];
+                        sc = sc_t[j];
+                    } else {
+                        corr = 128 * p.colsum[nc];
+                        sc = p.scale[nc % p.scale_n];
+                    }
                     const int n4 = n & ~3;
                     const uint32_t lane_off = n4 < p.N ? (uint32_t)((wm * Cfg::kWTM + 4 * lhi + (l32 & 3)) * pitch + n4) : kInvalidOffset;
                     asm volatile("" : "+v"(corr), "+v"(sc));
