@@ -286,6 +286,14 @@ extern "C" sparq_status sparq_conv_plan(const sparq_conv_desc* desc, const sparq
 
 namespace {
 
+// The gather kernel splits an output row number into (image, oy, ox) once per lane and tile with two divisions by
+// numbers fixed per launch.
+void set_row_division(GemmParams& p) {
+    p.div_wo = make_fastdiv((uint32_t)p.Wo);
+    p.div_ho = make_fastdiv((uint32_t)p.Ho);
+    p.rows_fit_31 = p.M < (1ll << 31) ? 1 : 0;
+}
+
 // Both convolution entry points: acc / out (with scale) as in sparq_conv_gemm, or y (with scale holding the
 // requantisation factors) as in sparq_conv_gemm_u8.
 sparq_status conv_launch(const uint8_t* x, const void* packed_w, const sparq_conv_desc* desc, const sparq_mode* mode,
@@ -337,6 +345,7 @@ sparq_status conv_launch(const uint8_t* x, const void* packed_w, const sparq_con
         p.sh = f.sh; p.sw = 1; p.ph = f.ph; p.pw = f.pw;
         p.rcp_c = 1.0f / 16.0f;
         p.rcp_kw = 1.0f / (float)f.KW;
+        set_row_division(p);
         p.luts = make_luts(8, 1);
         ConvGeom ft = f;
         ft.Np = g.Np;
@@ -418,6 +427,7 @@ sparq_status conv_launch(const uint8_t* x, const void* packed_w, const sparq_con
     p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw;
     p.rcp_c = 1.0f / (float)g.Cq;
     p.rcp_kw = 1.0f / (float)g.KW;
+    set_row_division(p);
     p.luts = make_luts(mode->window_bits, mode->shift_mask);
 
     return finish(pick_tile(g, tune, y != nullptr)(kind, p, s), fused_trim);

@@ -21,6 +21,7 @@
 #include <atomic>
 
 #include "sparq_common.h"
+#include "sparq_fastdiv.h"
 
 namespace sparq {
 
@@ -44,6 +45,8 @@ struct GemmParams {
     int H, W, C, Cq, Ho, Wo, KH, KW, sh, sw, ph, pw;   // C: channels per pixel in x; Cq: per tap in the packed weights
     int tiles_m, tiles_n;
     float rcp_c, rcp_kw;     // 1/Cq and 1/KW for the branch-free reduction-index decode
+    FastDiv div_wo, div_ho;  // output row -> (image, oy, ox) by multiply-high; valid when rows_fit_31
+    int rows_fit_31;         // M < 2^31
     TrimLuts luts;
 };
 
@@ -125,10 +128,20 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
         for (int i = 0; i < AC; ++i) {
             int64_t m = m0 + (tid >> 2) + i * (NT / 4);
             if (m >= p.M) m = p.M - 1;
-            const int ox = (int)(m % p.Wo);
-            const int64_t t = m / p.Wo;
-            const int oy = (int)(t % p.Ho);
-            const int b = (int)(t / p.Ho);
+            int ox, oy, b;
+            if (p.rows_fit_31) {                 // uniform; every shape of the paper's networks takes this side
+                const uint32_t mu = (uint32_t)m;
+                const uint32_t t = fastdiv(mu, p.div_wo);
+                const uint32_t img = fastdiv(t, p.div_ho);
+                ox = (int)(mu - t * (uint32_t)p.Wo);
+                oy = (int)(t - img * (uint32_t)p.Ho);
+                b = (int)img;
+            } else {
+                ox = (int)(m % p.Wo);
+                const int64_t t = m / p.Wo;
+                oy = (int)(t % p.Ho);
+                b = (int)(t / p.Ho);
+            }
             const int iy0 = oy * p.sh - p.ph, ix0 = ox * p.sw - p.pw;
             row_iy[i] = iy0;
             row_ix[i] = ix0;
