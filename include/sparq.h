@@ -239,10 +239,15 @@ sparq_status sparq_conv_gemm_packed(const void *packed_x, size_t packed_x_bytes,
  *   acc[m][n] = sum over taps and groups of ta * w_vals[..2g] + tb * w_vals[..2g+1],
  *   (ta, tb) = the pair rule of Eq. 2 on the two picked activations (each
  *   trimmed on its own when mode->pair is 0).
- * MI355X has no datapath that trims after a sparse selection; the result is
- * computed exactly on the dense int8 matrix cores over an expanded problem
- * (four dense multiply-accumulates per kept weight when vSPARQ is on; the
- * decompressed weights on the ordinary path when it is off).
+ * MI355X has no datapath that trims after a sparse selection; with vSPARQ on
+ * the result is computed exactly over an expanded problem (16 expanded channels
+ * per group of four, in which the kept weights are again 2:4 sparse); with it
+ * off the problem is the layer itself.  Where the layer's plan is the
+ * wave-specialised input-patch kernel (and, with vSPARQ off, the layer is a
+ * plain 8-bit one) the weights go to the sparse matrix instruction as its
+ * sparse operand; otherwise the decompressed weights run on the dense path.
+ * sparq_sparse24_plan reports which (a text line as from sparq_conv_plan plus
+ * "expanded_x4" and "sparse_mfma" / "dense_mfma").
  * packed: 256-byte aligned, sparq_sparse24_packed_bytes() bytes, filled once
  * by sparq_pack_weights_sparse24 for the same desc and mode; workspace:
  * 256-byte aligned, sparq_sparse24_workspace_bytes() bytes.  Everything else
@@ -256,6 +261,8 @@ sparq_status sparq_conv_gemm_sparse24(const uint8_t *x, const void *packed,
                                       const sparq_conv_desc *desc, const sparq_mode *mode,
                                       int32_t *acc, const float *scale, float *out,
                                       void *workspace, size_t workspace_bytes, void *stream);
+sparq_status sparq_sparse24_plan(const sparq_conv_desc *desc, const sparq_mode *mode,
+                                 char *text, size_t text_bytes);
 
 /* Test and tuning hook: overrides, for the whole process and until changed
  * again, which kernel and tiling the convolution entry points choose (the

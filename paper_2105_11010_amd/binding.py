@@ -52,6 +52,8 @@ def _load() -> ctypes.CDLL:
     L.sparq_workspace_bytes.restype = sz
     L.sparq_conv_plan.argtypes = [pd, pm, ctypes.c_char_p, sz]
     L.sparq_conv_plan.restype = ctypes.c_int
+    L.sparq_sparse24_plan.argtypes = [pd, pm, ctypes.c_char_p, sz]
+    L.sparq_sparse24_plan.restype = ctypes.c_int
     L.sparq_conv_gemm.argtypes = [vp, vp, pd, pm, vp, vp, vp, vp, sz, vp]
     L.sparq_conv_gemm.restype = ctypes.c_int
     L.sparq_conv_gemm_static_ws.argtypes = [vp, vp, pd, pm, vp, vp, vp, vp]
@@ -147,6 +149,13 @@ def sparq_conv_plan(d: SparqConvDesc, m: SparqMode) -> str:
     """Which kernel and tiling sparq_conv_gemm would use (a line of text for logs)."""
     buf = ctypes.create_string_buffer(256)
     _check(lib.sparq_conv_plan(ctypes.byref(d), ctypes.byref(m), buf, len(buf)), "sparq_conv_plan")
+    return buf.value.decode()
+
+
+def sparq_sparse24_plan(d: SparqConvDesc, m: SparqMode) -> str:
+    """Which kernel sparq_conv_gemm_sparse24 would use, and on which matrix instruction (a line of text for logs)."""
+    buf = ctypes.create_string_buffer(256)
+    _check(lib.sparq_sparse24_plan(ctypes.byref(d), ctypes.byref(m), buf, len(buf)), "sparq_sparse24_plan")
     return buf.value.decode()
 
 

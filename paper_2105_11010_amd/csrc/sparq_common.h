@@ -241,6 +241,10 @@ sparq_status launch_sparse24_expand_act(const uint8_t* x, uint8_t* xe, int64_t p
                                         hipStream_t stream);
 sparq_status launch_sparse24_expand_weights(const int8_t* vals, const uint8_t* idx, int8_t* dense, int64_t groups, bool expand,
                                             hipStream_t stream);
+// ... and the operands of the sparse matrix instruction (16 kept bytes + one word of positions per 32 reduction
+// indices) from dense weights [N][taps][C] with at most two non-zeros per aligned group of four channels.
+sparq_status launch_sparse24_pack_operand(const int8_t* dense, uint8_t* vals, uint32_t* pos, int N, int Np, int taps, int C,
+                                          int Cq, hipStream_t stream);
 
 // Implemented in sparq_packed_act.hip: the 8-bit values a packed activation tensor encodes.
 sparq_status launch_unpack_act(const void* packed, uint8_t* y, int64_t rows, int C, const sparq_mode* mode, int group,

@@ -51,26 +51,26 @@ TileLauncher pick_tile(const ConvGeom& g, const Tuning& tune, bool byte_output =
 }
 
 // ---- input-patch kernel: eligibility and variant choice --------------------------------------
-struct PatchVariant { int tn, ac, cbs; PatchLauncher fn; PatchLauncher fn_ws; };
+struct PatchVariant { int tn, ac, cbs; PatchLauncher fn; PatchLauncher fn_ws; PatchLauncher fn_sp; };   // plain, wave-specialised, sparse weights
 const PatchVariant kPatchVariants[] = {
-    {64, 2, 1, launch_patch_n64_a2c1, launch_patch_ws_n64_a2c1},
-    {64, 4, 1, launch_patch_n64_a4c1, launch_patch_ws_n64_a4c1},
-    {64, 8, 1, launch_patch_n64_a8c1, launch_patch_ws_n64_a8c1},
-    {64, 12, 1, launch_patch_n64_a12c1, launch_patch_ws_n64_a12c1},
-    {64, 4, 2, launch_patch_n64_a4c2, launch_patch_ws_n64_a4c2},
-    {64, 8, 4, launch_patch_n64_a8c4, launch_patch_ws_n64_a8c4},
-    {128, 2, 1, launch_patch_n128_a2c1, launch_patch_ws_n128_a2c1},
-    {128, 4, 1, launch_patch_n128_a4c1, launch_patch_ws_n128_a4c1},
-    {128, 8, 1, launch_patch_n128_a8c1, launch_patch_ws_n128_a8c1},
-    {128, 12, 1, launch_patch_n128_a12c1, launch_patch_ws_n128_a12c1},
-    {128, 4, 2, launch_patch_n128_a4c2, launch_patch_ws_n128_a4c2},
-    {128, 8, 4, launch_patch_n128_a8c4, launch_patch_ws_n128_a8c4},
-    {256, 2, 1, launch_patch_n256_a2c1, launch_patch_ws_n256_a2c1},
-    {256, 4, 1, launch_patch_n256_a4c1, launch_patch_ws_n256_a4c1},
-    {256, 8, 1, launch_patch_n256_a8c1, launch_patch_ws_n256_a8c1},
-    {256, 12, 1, launch_patch_n256_a12c1, launch_patch_ws_n256_a12c1},
-    {256, 4, 2, launch_patch_n256_a4c2, launch_patch_ws_n256_a4c2},
-    {256, 8, 4, launch_patch_n256_a8c4, launch_patch_ws_n256_a8c4},
+    {64, 2, 1, launch_patch_n64_a2c1, launch_patch_ws_n64_a2c1, launch_patch_sp_n64_a2c1},
+    {64, 4, 1, launch_patch_n64_a4c1, launch_patch_ws_n64_a4c1, launch_patch_sp_n64_a4c1},
+    {64, 8, 1, launch_patch_n64_a8c1, launch_patch_ws_n64_a8c1, launch_patch_sp_n64_a8c1},
+    {64, 12, 1, launch_patch_n64_a12c1, launch_patch_ws_n64_a12c1, launch_patch_sp_n64_a12c1},
+    {64, 4, 2, launch_patch_n64_a4c2, launch_patch_ws_n64_a4c2, launch_patch_sp_n64_a4c2},
+    {64, 8, 4, launch_patch_n64_a8c4, launch_patch_ws_n64_a8c4, launch_patch_sp_n64_a8c4},
+    {128, 2, 1, launch_patch_n128_a2c1, launch_patch_ws_n128_a2c1, launch_patch_sp_n128_a2c1},
+    {128, 4, 1, launch_patch_n128_a4c1, launch_patch_ws_n128_a4c1, launch_patch_sp_n128_a4c1},
+    {128, 8, 1, launch_patch_n128_a8c1, launch_patch_ws_n128_a8c1, launch_patch_sp_n128_a8c1},
+    {128, 12, 1, launch_patch_n128_a12c1, launch_patch_ws_n128_a12c1, launch_patch_sp_n128_a12c1},
+    {128, 4, 2, launch_patch_n128_a4c2, launch_patch_ws_n128_a4c2, launch_patch_sp_n128_a4c2},
+    {128, 8, 4, launch_patch_n128_a8c4, launch_patch_ws_n128_a8c4, launch_patch_sp_n128_a8c4},
+    {256, 2, 1, launch_patch_n256_a2c1, launch_patch_ws_n256_a2c1, launch_patch_sp_n256_a2c1},
+    {256, 4, 1, launch_patch_n256_a4c1, launch_patch_ws_n256_a4c1, launch_patch_sp_n256_a4c1},
+    {256, 8, 1, launch_patch_n256_a8c1, launch_patch_ws_n256_a8c1, launch_patch_sp_n256_a8c1},
+    {256, 12, 1, launch_patch_n256_a12c1, launch_patch_ws_n256_a12c1, launch_patch_sp_n256_a12c1},
+    {256, 4, 2, launch_patch_n256_a4c2, launch_patch_ws_n256_a4c2, launch_patch_sp_n256_a4c2},
+    {256, 8, 4, launch_patch_n256_a8c4, launch_patch_ws_n256_a8c4, launch_patch_sp_n256_a8c4},
 };
 
 // Largest patch (in pixels) any tile of this geometry needs.  Tile positions repeat relative to the
@@ -216,6 +216,13 @@ ConvPlan make_plan(const ConvGeom& g, const Tuning& tune) {
     return pl;
 }
 
+// 2:4 pruned weights run on the sparse matrix instruction when the layer's plan is the wave-specialised
+// input-patch kernel and the trim looks at one activation at a time (with pairing on the caller expands the
+// problem and `kind` is the plain one).
+bool sparse_plan(const ConvPlan& pl, TrimKind kind) {
+    return pl.patch && pl.ws && pl.variant->fn_sp && kind == kTrimNone;
+}
+
 }  // namespace
 
 extern "C" sparq_status sparq_set_tuning(const char* spec) {
@@ -296,9 +303,12 @@ void set_row_division(GemmParams& p) {
 
 // Both convolution entry points: acc / out (with scale) as in sparq_conv_gemm, or y (with scale holding the
 // requantisation factors) as in sparq_conv_gemm_u8.
+// sp: the weights as operands of the sparse matrix instruction as well (2:4 pruned layers); used when the plan is
+// the wave-specialised input-patch kernel, ignored otherwise.
+struct SparseOperand { const uint8_t* vals; const uint32_t* pos; };
 sparq_status conv_launch(const uint8_t* x, const void* packed_w, const sparq_conv_desc* desc, const sparq_mode* mode,
                          int32_t* acc, const float* scale, float* out, uint8_t* y, const sparq_mode* out_mode,
-                         void* workspace, size_t workspace_bytes, void* stream) {
+                         void* workspace, size_t workspace_bytes, void* stream, const SparseOperand* sp = nullptr) {
     ConvGeom g;
     if (!x || !packed_w || !conv_geom(desc, &g) || !mode_valid(mode)) return SPARQ_EINVAL;
     if (!acc && !out && !y) return SPARQ_EINVAL;
@@ -404,6 +414,14 @@ sparq_status conv_launch(const uint8_t* x, const void* packed_w, const sparq_con
             pfused = true;
         }
         q.trim_out = pfused ? 1 : 0;
+        if (sp && sparse_plan(pl, kind) && !y) {
+            PatchParams qs = q;
+            qs.wpk = sp->vals;
+            qs.widx = sp->pos;
+            qs.w_bytes = (uint32_t)((size_t)g.Kp * g.Np / 2);
+            const sparq_status st = pl.variant->fn_sp(kind, qs, pl.npix, s);
+            if (st != SPARQ_EUNSUPPORTED) return st;
+        }
         {
             const PatchLauncher fn = use_ws ? pl.variant->fn_ws : pl.variant->fn;
             const sparq_status st = fn(pkind, q, pl.npix, s);
@@ -534,14 +552,30 @@ bool sparse24_geometry(const sparq_conv_desc* desc, const sparq_mode* mode, spar
     return conv_geom(eff, &g);
 }
 const sparq_mode kNoPairPlain = {8, 1, 0, 0};
+
+// Layout of the buffer sparq_pack_weights_sparse24 fills: the dense packed tiles of the contracted problem, room
+// to decompress into, then the same weights as operands of the sparse matrix instruction (kept bytes, positions)
+// when the contracted problem's taps are 64-byte aligned (otherwise those two parts are empty).
+struct Sparse24Layout { size_t tiles, dense, vals, pos; bool sparse; };
+Sparse24Layout sparse24_layout(const sparq_conv_desc& eff) {
+    ConvGeom g;
+    conv_geom(&eff, &g);
+    Sparse24Layout L;
+    L.tiles = (size_t)round_up((int64_t)g.packed_bytes, 256);
+    L.dense = (size_t)round_up((int64_t)eff.N * eff.KH * eff.KW * eff.C, 256);
+    L.sparse = !g.fold && g.Cq % kStepK == 0;
+    L.vals = L.sparse ? (size_t)round_up((int64_t)g.Kp * g.Np / 2, 256) : 0;
+    L.pos = L.sparse ? (size_t)round_up((int64_t)g.Kp * g.Np / 8, 256) : 0;
+    return L;
+}
 }  // namespace
 
 extern "C" size_t sparq_sparse24_packed_bytes(const sparq_conv_desc* desc, const sparq_mode* mode) {
     sparq_conv_desc eff;
     bool expand;
     if (!sparse24_geometry(desc, mode, &eff, &expand)) return 0;
-    const size_t dense = (size_t)round_up((int64_t)eff.N * eff.KH * eff.KW * eff.C, 256);
-    return (size_t)round_up((int64_t)sparq_packed_bytes(&eff), 256) + dense;      // packed tiles + room to decompress into
+    const Sparse24Layout L = sparse24_layout(eff);
+    return L.tiles + L.dense + L.vals + L.pos;
 }
 
 extern "C" sparq_status sparq_pack_weights_sparse24(const int8_t* w_vals, const uint8_t* w_idx, const sparq_conv_desc* desc,
@@ -550,12 +584,18 @@ extern "C" sparq_status sparq_pack_weights_sparse24(const int8_t* w_vals, const 
     bool expand;
     if (!w_vals || !w_idx || !packed || !sparse24_geometry(desc, mode, &eff, &expand) || !aligned(packed, 256)) return SPARQ_EINVAL;
     if (packed_bytes < sparq_sparse24_packed_bytes(desc, mode)) return SPARQ_EWORKSPACE;
-    const size_t tiles = (size_t)round_up((int64_t)sparq_packed_bytes(&eff), 256);
-    int8_t* dense = static_cast<int8_t*>(packed) + tiles;
+    const Sparse24Layout L = sparse24_layout(eff);
+    int8_t* dense = static_cast<int8_t*>(packed) + L.tiles;
     const int64_t groups = (int64_t)desc->N * desc->KH * desc->KW * (desc->C / 4);
-    const sparq_status st = launch_sparse24_expand_weights(w_vals, w_idx, dense, groups, expand, static_cast<hipStream_t>(stream));
+    sparq_status st = launch_sparse24_expand_weights(w_vals, w_idx, dense, groups, expand, static_cast<hipStream_t>(stream));
     if (st != SPARQ_OK) return st;
-    return sparq_pack_weights(dense, &eff, packed, tiles, stream);
+    st = sparq_pack_weights(dense, &eff, packed, L.tiles, stream);
+    if (st != SPARQ_OK || !L.sparse) return st;
+    ConvGeom g;
+    conv_geom(&eff, &g);
+    uint8_t* vals = static_cast<uint8_t*>(packed) + L.tiles + L.dense;
+    return launch_sparse24_pack_operand(dense, vals, reinterpret_cast<uint32_t*>(vals + L.vals), eff.N, g.Np, eff.KH * eff.KW,
+                                        eff.C, g.Cq, static_cast<hipStream_t>(stream));
 }
 
 extern "C" size_t sparq_sparse24_workspace_bytes(const sparq_conv_desc* desc, const sparq_mode* mode) {
@@ -572,8 +612,12 @@ extern "C" sparq_status sparq_conv_gemm_sparse24(const uint8_t* x, const void* p
     sparq_conv_desc eff;
     bool expand;
     if (!x || !packed || (!acc && !out) || !sparse24_geometry(desc, mode, &eff, &expand)) return SPARQ_EINVAL;
+    const Sparse24Layout L = sparse24_layout(eff);
+    const uint8_t* sp_vals = static_cast<const uint8_t*>(packed) + L.tiles + L.dense;
+    const SparseOperand sp_op = {sp_vals, reinterpret_cast<const uint32_t*>(sp_vals + L.vals)};
+    const SparseOperand* sp = L.sparse ? &sp_op : nullptr;
     if (!expand)      // nothing depends on the partner: the decompressed weights, the ordinary path
-        return conv_launch(x, packed, desc, mode, acc, scale, out, nullptr, nullptr, workspace, workspace_bytes, stream);
+        return conv_launch(x, packed, desc, mode, acc, scale, out, nullptr, nullptr, workspace, workspace_bytes, stream, sp);
     if (!aligned(x, 4) || !workspace || !aligned(workspace, 256)) return SPARQ_EINVAL;
     if (workspace_bytes < sparq_sparse24_workspace_bytes(desc, mode)) return SPARQ_EWORKSPACE;
     const int64_t pixels = (int64_t)desc->B * desc->H * desc->W;
@@ -582,7 +626,23 @@ extern "C" sparq_status sparq_conv_gemm_sparse24(const uint8_t* x, const void* p
     const sparq_status st = launch_sparse24_expand_act(x, xe, pixels, desc->C, mode, static_cast<hipStream_t>(stream));
     if (st != SPARQ_OK) return st;
     return conv_launch(xe, packed, &eff, &kNoPairPlain, acc, scale, out, nullptr, nullptr, xe + x_room,
-                       workspace_bytes - x_room, stream);
+                       workspace_bytes - x_room, stream, sp);
+}
+
+extern "C" sparq_status sparq_sparse24_plan(const sparq_conv_desc* desc, const sparq_mode* mode, char* text, size_t text_bytes) {
+    sparq_conv_desc eff;
+    bool expand;
+    if (!text || text_bytes == 0 || !sparse24_geometry(desc, mode, &eff, &expand)) return SPARQ_EINVAL;
+    const sparq_mode* m = expand ? &kNoPairPlain : mode;
+    char line[200];
+    const sparq_status st = sparq_conv_plan(&eff, m, line, sizeof(line));
+    if (st != SPARQ_OK) return st;
+    ConvGeom g;
+    conv_geom(&eff, &g);
+    const ConvPlan pl = make_plan(g, current_tuning());
+    const bool smfmac = sparse24_layout(eff).sparse && sparse_plan(pl, trim_kind(m));
+    snprintf(text, text_bytes, "%s%s%s", line, expand ? " expanded_x4" : "", smfmac ? " sparse_mfma" : " dense_mfma");
+    return SPARQ_OK;
 }
 
 extern "C" sparq_status sparq_conv_gemm_u8(const uint8_t* x, const void* packed_w, const sparq_conv_desc* desc,

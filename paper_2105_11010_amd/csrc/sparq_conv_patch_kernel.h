@@ -32,12 +32,13 @@
 namespace sparq {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
 struct PatchParams {
     const uint8_t* x;        // activations, NHWC, C a multiple of 16
-    const uint8_t* wpk;      // packed weight tiles (taps padded to 64 channels)
+    const uint8_t* wpk;      // packed weight tiles (taps padded to 64 channels); sparse form: the kept weights
     const int32_t* colsum;   // sum_k w[n][k], Np entries
     int32_t* acc;            // [M][N] or null
     const float* scale;      // [N] or null
@@ -54,6 +55,8 @@ struct PatchParams {
     int tiles_m, tiles_n;
     PatchGeom g;
     TrimLuts luts;
+    const uint32_t* widx;    // sparse form only: positions of the kept weights, one word per 32 reduction indices
+                             // (last, so that the other forms' argument offsets, and with them their code, stay as they were)
 };
 
 constexpr int kLdsPerCu = 160 * 1024;
@@ -65,9 +68,14 @@ constexpr uint32_t kPatchInvalidOffset = 0x80000000u;   // beyond any buffer thi
 // fragments and weights and multiply.  A wavefront's loads return in order, so in the plain variant a weight wait
 // also waits for every older (slow, HBM) activation load; with separate wavefronts it does not, and the trim
 // arithmetic issues from other wavefronts while the matrix instructions run.
-template <int TN, int WGM, int WGN, int AC, int CBS, int WPC, bool WS = false>
+// SP: 2:4 pruned weights on the sparse matrix instruction (v_smfmac_i32_32x32x64_i8: the weights are its sparse
+// operand, two kept values of every four reduction indices plus their positions; the activations its dense
+// one), so a 64-byte step is one instruction per fragment pair instead of two and a lane ends up with 16 output
+// channels of one output pixel.  Wave-specialised form only, int32 / fp32 outputs only.
+template <int TN, int WGM, int WGN, int AC, int CBS, int WPC, bool WS = false, bool SP = false>
 struct PatchCfg {
     static constexpr bool kWaveSpecialised = WS;            // four more wavefronts do the loading, trimming and staging
+    static constexpr bool kSparse = SP;
     static constexpr int kTM = kPatchTM, kTN = TN, kWGM = WGM, kWGN = WGN, kAC = AC, kCBS = CBS, kWgPerCu = WPC;
     static constexpr int kMathThreads = 64 * WGM * WGN;
     static constexpr int kStageThreads = 256;
@@ -86,6 +94,7 @@ struct PatchCfg {
     static_assert(kTM % (32 * WGM) == 0 && TN % (32 * WGN) == 0, "tile must split into 32x32 fragments");
     static_assert(CBS == 1 || CBS == 2 || CBS == 4, "channel block");
     static_assert(AC >= 2 && AC % 2 == 0, "chunks per lane");
+    static_assert(!SP || (WS && kFN % 2 == 0), "sparse form: wave-specialised, an even number of channel fragments");
 };
 
 // bytes between planes: a multiple of 256 plus 256 / planes, so that the lanes that write one
@@ -98,7 +107,7 @@ template <int V> using int_c = std::integral_constant<int, V>;
 
 template <class Cfg, int KIND>
 __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256) void conv_patch_kernel(const PatchParams p) {
-    constexpr bool WS = Cfg::kWaveSpecialised;
+    constexpr bool WS = Cfg::kWaveSpecialised, SP = Cfg::kSparse;
     constexpr int NT = Cfg::kStageThreads, FM = Cfg::kFM, FN = Cfg::kFN, AC = Cfg::kAC, CBS = Cfg::kCBS, AS = Cfg::kAS;
     constexpr int PL = Cfg::kPlanes, TN = Cfg::kTN;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];     // [2][PL][plane_stride]
@@ -200,7 +209,7 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
         c_tm = c_tile / p.tiles_n;
         c_tn = c_tile - c_tm * p.tiles_n;
 #pragma unroll
-        for (int j = 0; j < FN; ++j) {
+        for (int j = 0; j < (SP ? 0 : FN); ++j) {    // (sparse form: 16 channels per lane and fragment, read in the epilogue)
             const int n = c_tn * TN + wn * Cfg::kWTN + j * 32 + l32;
             const int nc = n < p.N ? n : 0;
             // both constants are loaded on every path (a load under a condition makes the compiler put a full
@@ -249,8 +258,12 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
     //      the lane part of the address is fixed, everything else is uniform ----
     const __amdgpu_buffer_rsrc_t wrsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.wpk), 0, (int)p.w_bytes, 0x00020000);
+    //      Sparse form: lane (l32, lhi) of fragment j holds the 16 kept weights of w[...][32 indices at 32*lhi] and
+    //      one word with their positions (two bits each); same addressing with half the bytes per step.
+    const __amdgpu_buffer_rsrc_t irsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint32_t*>(p.widx), 0, SP ? (int)(p.w_bytes / 4) : 0, 0x00020000);
     const int wlane = (lhi * p.Np + wn * Cfg::kWTN + l32) * kChunk;
-    const int w_half = 2 * p.Np * kChunk;         // bytes between the two 32-channel halves of a step
+    const int w_half = (SP ? 1 : 2) * p.Np * kChunk;   // bytes between the two 32-index halves of a step
     const int grid_n = grid % p.tiles_n;
     int b_s = 0, b_cb = 0, b_tn = (int)blockIdx.x % p.tiles_n;
     auto next_b_offset = [&]() __attribute__((always_inline)) -> int {
@@ -266,12 +279,21 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
         b_tn -= b_tn >= p.tiles_n ? p.tiles_n : 0;
         return off;
     };
-    auto load_b = [&](v4i (&br)[FN], int wstep, int ks) __attribute__((always_inline)) {
+    // dense form: half ks of a step, all FN fragments; sparse form: the whole step of fragments ks*FN/2 .. +FN/2-1
+    auto load_b = [&](v4i (&br)[FN], int (&bi)[FN], int wstep, int ks) __attribute__((always_inline)) {
+        if constexpr (SP) {
 #pragma unroll
-        for (int j = 0; j < FN; ++j)
-            br[j] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, wlane, wstep + ks * w_half + j * 32 * kChunk, 0));
+            for (int jj = 0; jj < FN / 2; ++jj) {
+                const int soff = wstep + (ks * (FN / 2) + jj) * 32 * kChunk;
+                br[jj] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, wlane, soff, 0));
+                bi[jj] = (int)__builtin_amdgcn_raw_buffer_load_b32(irsrc, wlane / 4, soff / 4, 0);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+                br[j] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, wlane, wstep + ks * w_half + j * 32 * kChunk, 0));
+        }
     };
-
     v16i c[FM][FN];
     auto zero_acc = [&]() __attribute__((always_inline)) {
 #pragma unroll
@@ -282,6 +304,7 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
                 for (int v = 0; v < 16; ++v) c[i][j][v] = 0;
     };
     v4i b_reg[2][2][FN];          // weights of the current and the next step: [step parity][half][fragment]
+    int b_idx[2][2][FN];          // sparse form: their position words
     int w_next = 0;               // weight offset of the step two ahead, computed one step early
     v4i a_frag[2][2][FM];         // activation fragments: [step parity][half][fragment]
 
@@ -331,11 +354,11 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
     }
     {
         const int w0 = next_b_offset();
-        load_b(b_reg[0][0], w0, 0);
-        load_b(b_reg[0][1], w0, 1);
+        load_b(b_reg[0][0], b_idx[0][0], w0, 0);
+        load_b(b_reg[0][1], b_idx[0][1], w0, 1);
         const int w1 = next_b_offset();
-        load_b(b_reg[1][0], w1, 0);
-        load_b(b_reg[1][1], w1, 1);
+        load_b(b_reg[1][0], b_idx[1][0], w1, 0);
+        load_b(b_reg[1][1], b_idx[1][1], w1, 1);
         w_next = next_b_offset();
     }
     if constexpr (!WS) {
@@ -355,16 +378,27 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
     // One reduction step (64 channels of one tap).  A >= 0: the step also trims and stages chunks
     // 2A and 2A+1 of the next unit and requests the same chunks of the unit after it.  The two
     // scheduling regions keep the compiler from sinking the loads next to their uses.
-    auto step = [&](auto A_, v4i (&cur)[2][FM], v4i (&nxt)[2][FM], v4i (&br)[2][FN], const uint8_t* rbuf, uint8_t* sbuf) __attribute__((always_inline)) {
+    constexpr int NMF = SP ? FM * FN / 2 : FM * FN;   // matrix instructions per half of a step
+    auto step = [&](auto A_, v4i (&cur)[2][FM], v4i (&nxt)[2][FM], v4i (&br)[2][FN], int (&bi)[2][FN], const uint8_t* rbuf, uint8_t* sbuf) __attribute__((always_inline)) {
         constexpr int A = decltype(A_)::value;
         load_frags(nxt, rbuf);                      // f_off already points at the next step
         const int wstep = w_next;
+        if constexpr (SP) {
 #pragma unroll
-        for (int i = 0; i < FM; ++i)
+            for (int i = 0; i < FM; ++i) {
+                const v8i a = __builtin_shufflevector(cur[0][i], cur[1][i], 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
-            for (int j = 0; j < FN; ++j)
-                c[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur[0][i], br[0][j], c[i][j], 0, 0, 0);
-        load_b(br[0], wstep, 0);
+                for (int j = 0; j < FN / 2; ++j)
+                    c[i][j] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(br[0][j], a, c[i][j], bi[0][j], 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+                    c[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur[0][i], br[0][j], c[i][j], 0, 0, 0);
+        }
+        load_b(br[0], bi[0], wstep, 0);
         if constexpr (A >= 0) {
             stage_chunk(2 * A, sbuf);
             load_chunk(2 * A);
@@ -372,9 +406,9 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
             // plain step: the fragment reads and weight requests of this half are independent of its
             // matrix instructions; issue them in between rather than in front
 #pragma unroll
-            for (int k = 0; k < FM * FN; ++k) {
+            for (int k = 0; k < NMF; ++k) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                            // one matrix instruction
-                __builtin_amdgcn_sched_group_barrier(0x100, (2 * FM + FM * FN - 1) / (FM * FN), 0);   // fragment reads
+                __builtin_amdgcn_sched_group_barrier(0x100, (2 * FM + NMF - 1) / NMF, 0);     // fragment reads
                 __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);                            // their address adds
                 __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                            // a weight request
             }
@@ -384,20 +418,30 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
         // half's matrix instructions, where it is free, instead of in front of the next step's.
         advance_frag_cursor();
         w_next = next_b_offset();
+        if constexpr (SP) {
 #pragma unroll
-        for (int i = 0; i < FM; ++i)
+            for (int i = 0; i < FM; ++i) {
+                const v8i a = __builtin_shufflevector(cur[0][i], cur[1][i], 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
-            for (int j = 0; j < FN; ++j)
-                c[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur[1][i], br[1][j], c[i][j], 0, 0, 0);
-        load_b(br[1], wstep, 1);
+                for (int j = 0; j < FN / 2; ++j)
+                    c[i][FN / 2 + j] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(br[1][j], a, c[i][FN / 2 + j], bi[1][j], 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+                    c[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur[1][i], br[1][j], c[i][j], 0, 0, 0);
+        }
+        load_b(br[1], bi[1], wstep, 1);
         if constexpr (A >= 0 && 2 * A + 1 < AC) {
             stage_chunk(2 * A + 1, sbuf);
             load_chunk(2 * A + 1);
         }
 #pragma unroll
-        for (int k = 0; k < FM * FN; ++k) {
+        for (int k = 0; k < NMF; ++k) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                    // one matrix instruction
-            __builtin_amdgcn_sched_group_barrier(0x004, (40 + FM * FN - 1) / (FM * FN), 0);   // a slice of the scalar work
+            __builtin_amdgcn_sched_group_barrier(0x004, (40 + NMF - 1) / NMF, 0); // a slice of the scalar work
         }
         __builtin_amdgcn_sched_barrier(0);
     };
@@ -416,15 +460,15 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
         auto head = [&](auto self, auto s_) __attribute__((always_inline)) {
             constexpr int s0 = decltype(s_)::value;
             if constexpr (s0 < U0) {
-                step(int_c<(s0 < AS ? s0 : -1)>{}, a_frag[(P + s0) & 1], a_frag[(P + s0 + 1) & 1], b_reg[(P + s0) & 1], rbuf, sbuf);
+                step(int_c<(s0 < AS ? s0 : -1)>{}, a_frag[(P + s0) & 1], a_frag[(P + s0 + 1) & 1], b_reg[(P + s0) & 1], b_idx[(P + s0) & 1], rbuf, sbuf);
                 self(self, int_c<s0 + 1>{});
             }
         };
         head(head, int_c<0>{});
         constexpr int Q = (P + U0) & 1;
         for (int rem = p.nsteps - U0; rem > 0; rem -= 2) {
-            step(int_c<-1>{}, a_frag[Q], a_frag[Q ^ 1], b_reg[Q], rbuf, sbuf);
-            step(int_c<-1>{}, a_frag[Q ^ 1], a_frag[Q], b_reg[Q ^ 1], rbuf, sbuf);
+            step(int_c<-1>{}, a_frag[Q], a_frag[Q ^ 1], b_reg[Q], b_idx[Q], rbuf, sbuf);
+            step(int_c<-1>{}, a_frag[Q ^ 1], a_frag[Q], b_reg[Q ^ 1], b_idx[Q ^ 1], rbuf, sbuf);
         }
     };
 
@@ -446,7 +490,7 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
                 // branches, no 64-bit address arithmetic).  One copy per combination of outputs, chosen per tile.
                 const int rows = g.M - (int)m0 < kPatchTM ? g.M - (int)m0 : kPatchTM;
 #pragma unroll
-                for (int j = 0; j < FN; ++j) asm volatile("" : "+v"(corr[j]), "+v"(sc[j]));   // the tile's constants have landed from here on
+                for (int j = 0; j < (SP ? 0 : FN); ++j) asm volatile("" : "+v"(corr[j]), "+v"(sc[j]));   // the tile's constants have landed from here on
                 auto store_tile = [&](auto acc_, auto out_, auto u8_) __attribute__((always_inline)) {
                     constexpr bool kAcc = decltype(acc_)::value, kOut = decltype(out_)::value, kU8 = decltype(u8_)::value;
                     constexpr int kElem = kU8 ? 1 : 4;                 // bytes per stored result
@@ -511,6 +555,62 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
                             }
                         }
                 };
+                // Sparse form: the weights are the matrix instruction's row operand, so register v of fragment
+                // (i, j) is channel 8*(v/4) + 4*lhi + v%4 of pixel l32: a lane stores four consecutive channels of
+                // one pixel at a time (one 16-byte store when N is a multiple of 4), with the four channels'
+                // constants read here (plain loads at clamped indices, the same on every path).
+                auto store_tile_sp = [&](auto acc_, auto out_, auto vec_) __attribute__((always_inline)) {
+                    constexpr bool kAcc = decltype(acc_)::value, kOut = decltype(out_)::value, kVec = decltype(vec_)::value;
+                    const int pitch = p.N * 4;
+                    const int tile_bytes = rows * pitch;
+                    const __amdgpu_buffer_rsrc_t arsrc = __builtin_amdgcn_make_buffer_rsrc(
+                        kAcc ? (void*)(p.acc + m0 * p.N) : nullptr, 0, kAcc ? tile_bytes : 0, 0x00020000);
+                    const __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc(
+                        kOut ? (void*)(p.out + m0 * p.N) : nullptr, 0, kOut ? tile_bytes : 0, 0x00020000);
+                    const uint32_t row_off = (uint32_t)((wm * Cfg::kWTM + l32) * pitch);
+#pragma unroll
+                    for (int j = 0; j < FN; ++j)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const int nq = n0 + wn * Cfg::kWTN + j * 32 + 8 * q + 4 * lhi;
+                            int32_t cr[4];
+                            float sq[4];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const int nc = nq + e < p.N ? nq + e : 0;
+                                cr[e] = p.colsum[nc] * 128;
+                                sq[e] = scale_or_dummy[nc];
+                            }
+#pragma unroll
+                            for (int i = 0; i < FM; ++i) {
+                                const uint32_t off = row_off + (uint32_t)(i * 32 * pitch + nq * 4);
+                                v4i r, f;
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) {
+                                    r[e] = c[i][j][4 * q + e] + cr[e];
+                                    f[e] = __builtin_bit_cast(int, __fmul_rn((float)r[e], sq[e]));
+                                }
+                                if constexpr (kVec) {      // N % 4 == 0: the four channels are inside N together or not at all
+                                    const int o = (int)(nq < p.N ? off : 0x80000000u);
+                                    if constexpr (kAcc) __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, r), arsrc, o, 0, kResultStorePolicy);
+                                    if constexpr (kOut) __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, f), orsrc, o, 0, kResultStorePolicy);
+                                } else {
+#pragma unroll
+                                    for (int e = 0; e < 4; ++e) {
+                                        const int o = (int)(nq + e < p.N ? off + 4u * e : 0x80000000u);
+                                        if constexpr (kAcc) __builtin_amdgcn_raw_buffer_store_b32(r[e], arsrc, o, 0, kResultStorePolicy);
+                                        if constexpr (kOut) __builtin_amdgcn_raw_buffer_store_b32(f[e], orsrc, o, 0, kResultStorePolicy);
+                                    }
+                                }
+                            }
+                        }
+                };
+                if constexpr (SP) {
+                    const bool vec = (p.N & 3) == 0;
+                    if (p.acc && p.out) { if (vec) store_tile_sp(std::true_type{}, std::true_type{}, std::true_type{}); else store_tile_sp(std::true_type{}, std::true_type{}, std::false_type{}); }
+                    else if (p.out) { if (vec) store_tile_sp(std::false_type{}, std::true_type{}, std::true_type{}); else store_tile_sp(std::false_type{}, std::true_type{}, std::false_type{}); }
+                    else { if (vec) store_tile_sp(std::true_type{}, std::false_type{}, std::true_type{}); else store_tile_sp(std::true_type{}, std::false_type{}, std::false_type{}); }
+                } else
                 if (p.out_u8 && (p.N & 3) == 0) {
                     if (KIND != kTrimNone && p.trim_out) store_tile_u8_packed(std::true_type{});
                     else store_tile_u8_packed(std::false_type{});
@@ -554,6 +654,7 @@ sparq_status launch_patch_cfg(const PatchParams& p, int npix_max, hipStream_t s)
     q.plane_stride = patch_plane_stride(npix_max, Cfg::kPlanes);
     const int lds_bytes = 2 * Cfg::kPlanes * q.plane_stride + kChunk;     // two patch buffers + the dummy chunk
     if (p.g.rm_wo && !Cfg::kWaveSpecialised) return SPARQ_EUNSUPPORTED;
+    if (Cfg::kSparse != (p.widx != nullptr) || (Cfg::kSparse && p.out_u8)) return SPARQ_EUNSUPPORTED;
     if (!p.trim_in && !Cfg::kWaveSpecialised && KIND != kTrimNone) return SPARQ_EUNSUPPORTED;
     if ((int64_t)p.N * 4 * kPatchTM >= 0x7FFFFFFF) return SPARQ_EUNSUPPORTED;   // 32-bit offsets inside a tile of results
     if (npix_max > Cfg::kMaxPix || lds_bytes > kLdsPerCu || q.nsteps < Cfg::kUnrolled ||
@@ -596,6 +697,17 @@ sparq_status launch_patch_kind(TrimKind kind, const PatchParams& p, int npix_max
     }
 }
 
+// Sparse form: the trim variants that look at one activation at a time (with pairing on, the caller expands the
+// problem first and the kernel runs at plain 8 bits).
+template <class Cfg>
+sparq_status launch_patch_kind_sparse(TrimKind kind, const PatchParams& p, int npix_max, hipStream_t s) {
+    static_assert(Cfg::kSparse, "sparse configuration expected");
+    switch (kind) {
+        case kTrimNone: return launch_patch_cfg<Cfg, kTrimNone>(p, npix_max, s);
+        default: return SPARQ_EUNSUPPORTED;
+    }
+}
+
 // One translation unit per tile shape instantiates every trim variant and exports a launcher.
 typedef sparq_status (*PatchLauncher)(TrimKind, const PatchParams&, int, hipStream_t);
 #define SPARQ_DECLARE_PATCH(name) sparq_status name(TrimKind kind, const PatchParams& p, int npix_max, hipStream_t s)
@@ -617,6 +729,24 @@ SPARQ_DECLARE_PATCH(launch_patch_ws_n256_a8c1);
 SPARQ_DECLARE_PATCH(launch_patch_ws_n256_a12c1);
 SPARQ_DECLARE_PATCH(launch_patch_ws_n256_a4c2);
 SPARQ_DECLARE_PATCH(launch_patch_ws_n256_a8c4);
+SPARQ_DECLARE_PATCH(launch_patch_sp_n64_a2c1);
+SPARQ_DECLARE_PATCH(launch_patch_sp_n64_a4c1);
+SPARQ_DECLARE_PATCH(launch_patch_sp_n64_a8c1);
+SPARQ_DECLARE_PATCH(launch_patch_sp_n64_a12c1);
+SPARQ_DECLARE_PATCH(launch_patch_sp_n64_a4c2);
+SPARQ_DECLARE_PATCH(launch_patch_sp_n64_a8c4);
+SPARQ_DECLARE_PATCH(launch_patch_sp_n128_a2c1);
+SPARQ_DECLARE_PATCH(launch_patch_sp_n128_a4c1);
+SPARQ_DECLARE_PATCH(launch_patch_sp_n128_a8c1);
+SPARQ_DECLARE_PATCH(launch_patch_sp_n128_a12c1);
+SPARQ_DECLARE_PATCH(launch_patch_sp_n128_a4c2);
+SPARQ_DECLARE_PATCH(launch_patch_sp_n128_a8c4);
+SPARQ_DECLARE_PATCH(launch_patch_sp_n256_a2c1);
+SPARQ_DECLARE_PATCH(launch_patch_sp_n256_a4c1);
+SPARQ_DECLARE_PATCH(launch_patch_sp_n256_a8c1);
+SPARQ_DECLARE_PATCH(launch_patch_sp_n256_a12c1);
+SPARQ_DECLARE_PATCH(launch_patch_sp_n256_a4c2);
+SPARQ_DECLARE_PATCH(launch_patch_sp_n256_a8c4);
 SPARQ_DECLARE_PATCH(launch_patch_n64_a12c1);
 SPARQ_DECLARE_PATCH(launch_patch_n128_a12c1);
 SPARQ_DECLARE_PATCH(launch_patch_n256_a12c1);

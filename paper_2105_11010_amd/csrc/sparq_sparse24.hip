@@ -88,7 +88,56 @@ __global__ __launch_bounds__(kSpThreads) void expand_weights_kernel(const int8_t
     }
 }
 
+// Operands of the sparse matrix instruction from dense weights w[N][taps][C] that hold at most two non-zeros in
+// every aligned group of four channels (the expanded groups above do, and so do decompressed 2:4 weights).
+// One lane per (64-index reduction step, half h, output channel n < Np): the 32 weights w[n][step*64 + 32h ..]
+// -- taps padded to Cq channels, as in the dense packed tiles -- become 16 kept bytes (two per group of four, in
+// position order) and one word of positions (bits [4g+1:4g] and [4g+3:4g+2] for group g, first < second, which
+// is the layout v_smfmac_i32_32x32x64_i8 reads from lane (n % 32, h)).  Groups with fewer than two non-zeros keep
+// zeros at unused positions.  vals[step][h][Np][16], pos[step][h][Np].
+__global__ __launch_bounds__(kSpThreads) void pack_sparse_operand_kernel(const int8_t* __restrict__ w, uint4* __restrict__ vals,
+                                                                          uint32_t* __restrict__ pos, int N, int Np, int taps,
+                                                                          int C, int Cq, int64_t items) {
+    const int64_t stride = (int64_t)gridDim.x * kSpThreads;
+    const int steps_tap = Cq / 64;
+    for (int64_t it = (int64_t)blockIdx.x * kSpThreads + threadIdx.x; it < items; it += stride) {
+        const int n = (int)(it % Np);
+        const int64_t sh = it / Np;
+        const int h = (int)(sh & 1);
+        const int64_t step = sh >> 1;
+        const int tap = (int)(step / steps_tap);
+        const int c0 = (int)(step % steps_tap) * 64 + 32 * h;
+        uint32_t out[4] = {0, 0, 0, 0}, word = 0;
+#pragma unroll
+        for (int g = 0; g < 8; ++g) {
+            const int c = c0 + 4 * g;
+            uint32_t v = 0;
+            if (n < N && c < C) v = *reinterpret_cast<const uint32_t*>(w + ((int64_t)n * taps + tap) * C + c);   // C % 4 == 0
+            int p0 = -1, p1 = -1;
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if ((v >> (8 * k)) & 255u) { if (p0 < 0) p0 = k; else if (p1 < 0) p1 = k; }
+            if (p0 < 0) { p0 = 0; p1 = 1; }
+            else if (p1 < 0) { if (p0 == 3) { p1 = 3; p0 = 2; } else p1 = 3; }
+            const uint32_t b0 = (v >> (8 * p0)) & 255u, b1 = (v >> (8 * p1)) & 255u;
+            const int e = 2 * g;
+            out[e >> 2] |= (b0 << (8 * (e & 3))) | (b1 << (8 * ((e + 1) & 3)));
+            word |= (uint32_t)(p0 | (p1 << 2)) << (4 * g);
+        }
+        vals[it] = make_uint4(out[0], out[1], out[2], out[3]);
+        pos[it] = word;
+    }
+}
+
 }  // namespace
+
+sparq_status launch_sparse24_pack_operand(const int8_t* dense, uint8_t* vals, uint32_t* pos, int N, int Np, int taps, int C,
+                                          int Cq, hipStream_t s) {
+    const int64_t items = (int64_t)taps * (Cq / 64) * 2 * Np;
+    if (items == 0) return SPARQ_OK;
+    pack_sparse_operand_kernel<<<sp_grid(items), kSpThreads, 0, s>>>(dense, reinterpret_cast<uint4*>(vals), pos, N, Np, taps, C, Cq, items);
+    return launch_status();
+}
 
 sparq_status launch_sparse24_expand_act(const uint8_t* x, uint8_t* xe, int64_t pixels, int C, const sparq_mode* mode,
                                         hipStream_t s) {

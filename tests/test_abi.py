@@ -29,7 +29,7 @@ def test_header_declares_the_boundary():
     assert declared_symbols() == ["sparq_conv_gemm", "sparq_conv_gemm_packed", "sparq_conv_gemm_sparse24", "sparq_conv_gemm_static_ws", "sparq_conv_gemm_u8",
                                   "sparq_conv_packed_workspace_bytes", "sparq_conv_plan", "sparq_dequant", "sparq_pack_act",
                                   "sparq_pack_weights", "sparq_pack_weights_sparse24", "sparq_packed_act_bytes", "sparq_packed_bytes", "sparq_requant", "sparq_set_tuning",
-                                  "sparq_sparse24_packed_bytes", "sparq_sparse24_workspace_bytes",
+                                  "sparq_sparse24_packed_bytes", "sparq_sparse24_plan", "sparq_sparse24_workspace_bytes",
                                   "sparq_strerror", "sparq_trim", "sparq_unpack_act", "sparq_workspace_bytes"]
 
 

@@ -24,6 +24,23 @@ LAYERS = [
 ]
 
 
+# shapes for the sparse matrix instruction's kernel: ragged pixel and channel tiles, channel counts that are not a
+# multiple of 4 (scalar result stores), strides, wide layers (256-channel tiles), long reductions
+SPARSE_MFMA_LAYERS = [
+    S.ConvLayer("spm_3x3_64_50", 2, 13, 11, 64, 50, 3, 3, (1, 1), (1, 1), 0.5, M45),
+    S.ConvLayer("spm_3x3_32_300", 3, 12, 12, 32, 300, 3, 3, (1, 1), (1, 1), 0.4, M45),
+    S.ConvLayer("spm_1x1s2_64_130", 2, 15, 15, 64, 130, 1, 1, (2, 2), (0, 0), 0.5, M45),
+    S.ConvLayer("spm_3x3s2_48_72", 2, 17, 17, 48, 72, 3, 3, (2, 2), (1, 1), 0.6, S.Mode(4, S.OPT3, 0, 1)),
+    S.ConvLayer("spm_5x5_16_33", 1, 20, 20, 16, 33, 5, 5, (1, 1), (2, 2), 0.5, S.Mode(3, S.OPT6_3B, 1, 1)),
+    S.ConvLayer("spm_1x1_512_256", 1, 23, 23, 512, 256, 1, 1, (1, 1), (0, 0), 0.5, M45),
+    S.ConvLayer("spm_3x3_128_64_plain8", 2, 19, 19, 128, 64, 3, 3, (1, 1), (1, 1), 0.5, S.PLAIN8),
+    S.ConvLayer("spm_1x1_96_64", 2, 15, 15, 96, 64, 1, 1, (1, 1), (0, 0), 0.5, M45),
+    S.ConvLayer("spm_1x1_192_100_plain8", 2, 19, 19, 192, 100, 1, 1, (1, 1), (0, 0), 0.5, S.PLAIN8),
+]
+FORMS = [None, "path=gather", "path=patch,patch_ws=1", "path=patch,patch_ws=1,patch_tn=64", "path=patch,patch_ws=1,patch_tn=128",
+         "path=patch,patch_ws=1,patch_tn=256"]
+
+
 @pytest.fixture(scope="module")
 def sq():
     assert torch.cuda.is_available(), "GPU tests need a device"
@@ -57,6 +74,35 @@ def test_sparse24_convolution(sq, oracle, layer):
     ref_acc, ref_out = oracle.conv_gemm_sparse24(x, wv, wi, layer.stride, layer.pad, scale=sc, **layer.mode.kwargs())
     assert np.array_equal(acc, ref_acc), f"{layer.name}: int32 accumulators differ from the oracle"
     assert np.all(np.abs(out.astype(np.float64) - ref_out) <= 1e-6 * np.abs(ref_out))
+
+
+@pytest.mark.parametrize("layer", SPARSE_MFMA_LAYERS, ids=lambda l: l.name)
+def test_sparse24_on_the_sparse_matrix_instruction(sq, oracle, layer):
+    """Every kernel form the layer can take (the rules' choice, the gather kernel, the wave-specialised input-patch
+    kernel at each tile width) against the oracle; the patch forms must report the sparse matrix instruction."""
+    rng = S.rng_for(10, 100 + SPARSE_MFMA_LAYERS.index(layer))
+    x = S.gen_activations(layer.x_shape(), layer.zf, rng)
+    wv, wi = S.gen_sparse24_weights(layer.w_shape(), rng)
+    sc = S.gen_scales(layer.N, rng)
+    ref_acc, ref_out = oracle.conv_gemm_sparse24(x, wv, wi, layer.stride, layer.pad, scale=sc, **layer.mode.kwargs())
+    d = sq.conv_desc(layer.B, layer.H, layer.W, layer.C, layer.N, layer.KH, layer.KW, layer.stride, layer.pad)
+    m = sq.mode(*layer.mode.astuple())
+    seen = set()
+    try:
+        for spec in FORMS:
+            sq.sparq_set_tuning(spec)
+            plan = sq.sparq_sparse24_plan(d, m)
+            if spec and "patch" in spec:
+                assert "conv_patch_kernel" not in plan or plan.endswith("sparse_mfma"), plan
+            if spec == "path=gather":
+                assert plan.endswith("dense_mfma"), plan
+            seen.add(plan)
+            acc, out = run_sparse(sq, layer, x, wv, wi, sc)
+            assert np.array_equal(acc, ref_acc), f"{layer.name} [{plan}]: int32 accumulators differ from the oracle"
+            assert np.all(np.abs(out.astype(np.float64) - ref_out) <= 1e-6 * np.abs(ref_out)), plan
+    finally:
+        sq.sparq_set_tuning(None)
+    assert any(p.endswith("sparse_mfma") for p in seen), seen
 
 
 def test_extreme_values(sq, oracle):
