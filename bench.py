@@ -524,9 +524,11 @@ def main():
             ws = torch.empty(max(sq.sparq_sparse24_workspace_bytes(dom["d"], pm), 1), dtype=torch.uint8, device=dev)
             ms6 = time_calls(torch, lambda i: sq.sparq_conv_gemm_sparse24(dom["x"], sp, dom["d"], pm, scale=dom["sc"], out=dom["out"],
                                                                           workspace=ws), args.warmup, args.steps)
-            e = entry(wl_name + ", 2:4 pruned weights (activations picked by the kept weights, then paired; emulated on the "
-                                "dense matrix cores over an expanded problem)", [L], ms6, 4)
-            e["note"] = "value counts the dense layer's operations; the emulation multiplies 4x the channels when pairing is on"
+            e = entry(wl_name + ", 2:4 pruned weights (activations picked by the kept weights, then paired: an expanded problem "
+                                "with 4x the channels whose weights are again 2:4 sparse)", [L], ms6, 4)
+            e["plan"] = sq.sparq_sparse24_plan(dom["d"], pm)
+            e["note"] = ("value counts the dense layer's operations; with pairing on the expanded problem holds 4x the channels, "
+                         "on the sparse matrix instruction (plan ends in sparse_mfma) that is 2x the dense layer's matrix instructions")
             also.append(e)
             del wvd, wid, sp, ws
         torch.cuda.empty_cache()

@@ -1,5 +1,6 @@
-// 2:4 structured weight sparsity (Section 4, sparse tensor core; Section 5.3) as an exact emulation on the dense
-// int8 matrix cores.
+// 2:4 structured weight sparsity (Section 4, sparse tensor core; Section 5.3): the expansion that makes the
+// pair-dependent trim an ordinary contraction, and the operand formats of the dense and the sparse matrix
+// instruction for it.
 //
 // Of every four adjacent weights along the input channels an output channel keeps two, stored with their
 // coordinates; the coordinates pick two of the four activations, and the picked two form that output channel's
@@ -11,11 +12,11 @@
 // the value channel n sees is  B_i + F_ij,  F_ij = (x_j == 0 ? W_i : T_i) - B_i >= 0,  j = its partner.  So a
 // group of four input channels is expanded into 16 unsigned bytes -- B_0..B_3 and the twelve F_ij (i, then j
 // ascending) -- and an output channel's two kept weights are written at the four matching places of a
-// 16-byte weight group (w_i at B_i and at F_ij).  The dense plain-8-bit contraction of the expanded tensors is
-// then exactly the sparse, pair-trimmed dot product.  The cost is four dense multiply-accumulates per kept
-// weight: SPARQ's pairing on top of a sparse tensor core is custom hardware, this is its arithmetic.
-// With vSPARQ off (or a plain 8-bit layer) nothing depends on the partner: the weights are decompressed and the
-// ordinary kernels run.
+// 16-byte weight group (w_i at B_i and at F_ij).  The plain-8-bit contraction of the expanded tensors is
+// then exactly the sparse, pair-trimmed dot product.  The expanded weights are again 2:4 sparse (two non-zeros in
+// 16), so they also go, as kept bytes plus positions, to the sparse matrix instruction (the SP form of the
+// input-patch kernel): two instructions' worth of work per kept weight pair instead of four dense ones.
+// With vSPARQ off (or a plain 8-bit layer) nothing depends on the partner: the problem is the layer itself.
 #include "sparq_common.h"
 
 namespace sparq {
