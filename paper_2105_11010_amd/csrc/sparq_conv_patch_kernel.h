@@ -60,10 +60,8 @@ struct PatchParams {
 };
 
 constexpr int kLdsPerCu = 160 * 1024;
-// Result stores of the sparse form: the ordinary cache policy.  Its lanes write 16-byte pieces of 32 different rows
-// per instruction, and the pieces of a 128-byte line arrive over four instructions: L2 has to merge them (with the
-// non-temporal policy of the other forms the same kernel took 0.20 instead of 0.14 ms on the default layer).
-constexpr int kSparseStorePolicy = 0;
+constexpr int kSparseRowPitch = 272;               // LDS row of 64 fp32 results, padded so that the lanes' 16-byte writes spread over the banks
+constexpr int kSparseEpilogueLds = 4 * 32 * kSparseRowPitch;
 constexpr uint32_t kPatchInvalidOffset = 0x80000000u;   // beyond any buffer this kernel accepts (< 2 GiB)
 
 // TN output channels per workgroup, WGM x WGN wavefronts, AC 16-byte patch chunks per lane and
@@ -213,7 +211,7 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
         c_tm = c_tile / p.tiles_n;
         c_tn = c_tile - c_tm * p.tiles_n;
 #pragma unroll
-        for (int j = 0; j < (SP ? 0 : FN); ++j) {    // (sparse form: 16 channels per lane and fragment, read in the epilogue)
+        for (int j = 0; j < (SP ? 0 : FN); ++j) {
             const int n = c_tn * TN + wn * Cfg::kWTN + j * 32 + l32;
             const int nc = n < p.N ? n : 0;
             // both constants are loaded on every path (a load under a condition makes the compiler put a full
@@ -560,9 +558,12 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
                         }
                 };
                 // Sparse form: the weights are the matrix instruction's row operand, so register v of fragment
-                // (i, j) is channel 8*(v/4) + 4*lhi + v%4 of pixel l32: a lane stores four consecutive channels of
-                // one pixel at a time (one 16-byte store when N is a multiple of 4), with the four channels'
-                // constants read here (plain loads at clamped indices, the same on every path).
+                // (i, j) is channel 8*(v/4) + 4*lhi + v%4 of pixel l32.  Stored straight from the registers that is
+                // 16 bytes per lane to 32 different rows per instruction; instead the accumulators go through a
+                // wavefront-private LDS area ([32 pixels][64 channels] int32, rows padded to 272 bytes) and leave
+                // as whole rows: a lane reads 16 bytes of a row, applies its four channels' constants and every
+                // store instruction writes four 256-byte runs.  The LDS queue of a wavefront is in order, so its
+                // reads see its writes without a barrier.
                 auto store_tile_sp = [&](auto acc_, auto out_, auto vec_) __attribute__((always_inline)) {
                     constexpr bool kAcc = decltype(acc_)::value, kOut = decltype(out_)::value, kVec = decltype(vec_)::value;
                     const int pitch = p.N * 4;
@@ -571,43 +572,60 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
                         kAcc ? (void*)(p.acc + m0 * p.N) : nullptr, 0, kAcc ? tile_bytes : 0, 0x00020000);
                     const __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc(
                         kOut ? (void*)(p.out + m0 * p.N) : nullptr, 0, kOut ? tile_bytes : 0, 0x00020000);
-                    const uint32_t row_off = (uint32_t)((wm * Cfg::kWTM + l32) * pitch);
+                    // (the lane number made opaque here: otherwise the addresses below are computed once, ahead of
+                    // the tile loop, and held in registers the step loop then has to spill)
+                    int le = lane;
+                    asm volatile("" : "+v"(le));
+                    uint8_t* xr = lds + 2 * buf_bytes + kChunk + wave * (32 * kSparseRowPitch);
+                    uint8_t* xw = xr + (le & 31) * kSparseRowPitch + 16 * (le >> 5);
+                    const uint8_t* xrd = xr + (le >> 4) * kSparseRowPitch + (le & 15) * 16;
+                    const int nrun = n0 + wn * Cfg::kWTN + (le & 15) * 4;            // first channel of this lane's 16 bytes
+                    const uint32_t run_off = (uint32_t)((wm * Cfg::kWTM + (le >> 4)) * pitch + nrun * 4);
+                    // the lane's four channels' constants: requested here, ahead of every store (a request between
+                    // stores would wait for their round trips) and not at the tile's start (the step loop has no
+                    // registers to spare for them)
+                    static_assert(!SP || Cfg::kWTN == 64, "64 channels per wavefront");
+                    int32_t corr4[4];
+                    float sc4[4];
 #pragma unroll
-                    for (int j = 0; j < FN; ++j)
+                    for (int e = 0; e < 4; ++e) {
+                        const int nc = nrun + e < p.N ? nrun + e : 0;
+                        corr4[e] = p.colsum[nc] * 128;
+                        sc4[e] = scale_or_dummy[nc];
+                    }
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const int nq = n0 + wn * Cfg::kWTN + j * 32 + 8 * q + 4 * lhi;
-                            int32_t cr[4];
-                            float sq[4];
+                    for (int i = 0; i < FM; ++i) {
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                const int nc = nq + e < p.N ? nq + e : 0;
-                                cr[e] = p.colsum[nc] * 128;
-                                sq[e] = scale_or_dummy[nc];
+                        for (int j = 0; j < FN; ++j)
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) {
+                                const v4i r = {c[i][j][4 * q], c[i][j][4 * q + 1], c[i][j][4 * q + 2], c[i][j][4 * q + 3]};
+                                *reinterpret_cast<v4i*>(xw + (j * 32 + 8 * q) * 4) = r;
                             }
 #pragma unroll
-                            for (int i = 0; i < FM; ++i) {
-                                const uint32_t off = row_off + (uint32_t)(i * 32 * pitch + nq * 4);
-                                v4i r, f;
+                        for (int k = 0; k < 8; ++k) {
+                            v4i r = *reinterpret_cast<const v4i*>(xrd + 4 * k * kSparseRowPitch);
+                            v4i f;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                r[e] += corr4[e];
+                                f[e] = __builtin_bit_cast(int, __fmul_rn((float)r[e], sc4[e]));
+                            }
+                            const uint32_t off = run_off + (uint32_t)((i * 32 + 4 * k) * pitch);
+                            if constexpr (kVec) {      // N % 4 == 0: the four channels are inside N together or not at all
+                                const int o = (int)(nrun < p.N ? off : 0x80000000u);
+                                if constexpr (kAcc) __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, r), arsrc, o, 0, kResultStorePolicy);
+                                if constexpr (kOut) __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, f), orsrc, o, 0, kResultStorePolicy);
+                            } else {
 #pragma unroll
                                 for (int e = 0; e < 4; ++e) {
-                                    r[e] = c[i][j][4 * q + e] + cr[e];
-                                    f[e] = __builtin_bit_cast(int, __fmul_rn((float)r[e], sq[e]));
-                                }
-                                if constexpr (kVec) {      // N % 4 == 0: the four channels are inside N together or not at all
-                                    const int o = (int)(nq < p.N ? off : 0x80000000u);
-                                    if constexpr (kAcc) __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, r), arsrc, o, 0, kSparseStorePolicy);
-                                    if constexpr (kOut) __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, f), orsrc, o, 0, kSparseStorePolicy);
-                                } else {
-#pragma unroll
-                                    for (int e = 0; e < 4; ++e) {
-                                        const int o = (int)(nq + e < p.N ? off + 4u * e : 0x80000000u);
-                                        if constexpr (kAcc) __builtin_amdgcn_raw_buffer_store_b32(r[e], arsrc, o, 0, kSparseStorePolicy);
-                                        if constexpr (kOut) __builtin_amdgcn_raw_buffer_store_b32(f[e], orsrc, o, 0, kSparseStorePolicy);
-                                    }
+                                    const int o = (int)(nrun + e < p.N ? off + 4u * e : 0x80000000u);
+                                    if constexpr (kAcc) __builtin_amdgcn_raw_buffer_store_b32(r[e], arsrc, o, 0, kResultStorePolicy);
+                                    if constexpr (kOut) __builtin_amdgcn_raw_buffer_store_b32(f[e], orsrc, o, 0, kResultStorePolicy);
                                 }
                             }
                         }
+                    }
                 };
                 if constexpr (SP) {
                     const bool vec = (p.N & 3) == 0;
@@ -656,7 +674,8 @@ template <class Cfg, int KIND>
 sparq_status launch_patch_cfg(const PatchParams& p, int npix_max, hipStream_t s) {
     PatchParams q = p;
     q.plane_stride = patch_plane_stride(npix_max, Cfg::kPlanes);
-    const int lds_bytes = 2 * Cfg::kPlanes * q.plane_stride + kChunk;     // two patch buffers + the dummy chunk
+    const int lds_bytes = 2 * Cfg::kPlanes * q.plane_stride + kChunk +    // two patch buffers + the dummy chunk
+                          (Cfg::kSparse ? kSparseEpilogueLds : 0);         // + the sparse form's result rows
     if (p.g.rm_wo && !Cfg::kWaveSpecialised) return SPARQ_EUNSUPPORTED;
     if (Cfg::kSparse != (p.widx != nullptr) || (Cfg::kSparse && p.out_u8)) return SPARQ_EUNSUPPORTED;
     if (!p.trim_in && !Cfg::kWaveSpecialised && KIND != kTrimNone) return SPARQ_EUNSUPPORTED;
