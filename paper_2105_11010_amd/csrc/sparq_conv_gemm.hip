@@ -217,10 +217,11 @@ ConvPlan make_plan(const ConvGeom& g, const Tuning& tune) {
 }
 
 // 2:4 pruned weights run on the sparse matrix instruction when the layer's plan is the wave-specialised
-// input-patch kernel and the trim looks at one activation at a time (with pairing on the caller expands the
-// problem and `kind` is the plain one).
+// input-patch kernel and the trim looks at one activation at a time (with pairing on, the caller expands the
+// problem and `kind` is the plain one; with it off the staging wavefronts trim as in the dense form).
 bool sparse_plan(const ConvPlan& pl, TrimKind kind) {
-    return pl.patch && pl.ws && pl.variant->fn_sp && kind == kTrimNone;
+    const bool single = kind == kTrimNone || kind == kTrimFloor || kind == kTrimRound || kind == kTrimRound4;
+    return pl.patch && pl.ws && pl.variant->fn_sp && single;
 }
 
 }  // namespace
@@ -640,7 +641,8 @@ extern "C" sparq_status sparq_sparse24_plan(const sparq_conv_desc* desc, const s
     ConvGeom g;
     conv_geom(&eff, &g);
     const ConvPlan pl = make_plan(g, current_tuning());
-    const bool smfmac = sparse24_layout(eff).sparse && sparse_plan(pl, trim_kind(m));
+    const TrimKind kind = (g.fold || g.Cp != g.C) ? kTrimNone : trim_kind(m);     // a padded copy is trimmed by its pre-pass
+    const bool smfmac = sparse24_layout(eff).sparse && sparse_plan(pl, kind);
     snprintf(text, text_bytes, "%s%s%s", line, expand ? " expanded_x4" : "", smfmac ? " sparse_mfma" : " dense_mfma");
     return SPARQ_OK;
 }

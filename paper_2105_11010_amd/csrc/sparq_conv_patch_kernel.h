@@ -727,6 +727,9 @@ sparq_status launch_patch_kind_sparse(TrimKind kind, const PatchParams& p, int n
     static_assert(Cfg::kSparse, "sparse configuration expected");
     switch (kind) {
         case kTrimNone: return launch_patch_cfg<Cfg, kTrimNone>(p, npix_max, s);
+        case kTrimFloor: return launch_patch_cfg<Cfg, kTrimFloor>(p, npix_max, s);
+        case kTrimRound: return launch_patch_cfg<Cfg, kTrimRound>(p, npix_max, s);
+        case kTrimRound4: return launch_patch_cfg<Cfg, kTrimRound4>(p, npix_max, s);
         default: return SPARQ_EUNSUPPORTED;
     }
 }

@@ -35,6 +35,10 @@ SPARSE_MFMA_LAYERS = [
     S.ConvLayer("spm_1x1_512_256", 1, 23, 23, 512, 256, 1, 1, (1, 1), (0, 0), 0.5, M45),
     S.ConvLayer("spm_3x3_128_64_plain8", 2, 19, 19, 128, 64, 3, 3, (1, 1), (1, 1), 0.5, S.PLAIN8),
     S.ConvLayer("spm_1x1_96_64", 2, 15, 15, 96, 64, 1, 1, (1, 1), (0, 0), 0.5, M45),
+    S.ConvLayer("spm_3x3_64_72_novS_round4", 2, 17, 15, 64, 72, 3, 3, (1, 1), (1, 1), 0.5, S.Mode(4, S.OPT5, 1, 0)),
+    S.ConvLayer("spm_3x3s2_128_50_novS_floor", 2, 17, 17, 128, 50, 3, 3, (2, 2), (1, 1), 0.4, S.Mode(4, S.OPT3, 0, 0)),
+    S.ConvLayer("spm_1x1_256_260_novS_round3", 2, 15, 15, 256, 260, 1, 1, (1, 1), (0, 0), 0.5, S.Mode(3, S.OPT6_3B, 1, 0)),
+    S.ConvLayer("spm_1x7_64_64_novS_floor2", 2, 17, 17, 64, 64, 1, 7, (1, 1), (0, 3), 0.5, S.Mode(2, S.OPT7_2B, 0, 0)),
     S.ConvLayer("spm_1x1_192_100_plain8", 2, 19, 19, 192, 100, 1, 1, (1, 1), (0, 0), 0.5, S.PLAIN8),
 ]
 FORMS = [None, "path=gather", "path=patch,patch_ws=1", "path=patch,patch_ws=1,patch_tn=64", "path=patch,patch_ws=1,patch_tn=128",
