@@ -243,9 +243,9 @@ sparq_status sparq_conv_gemm_packed(const void *packed_x, size_t packed_x_bytes,
  * the result is computed exactly over an expanded problem (16 expanded channels
  * per group of four, in which the kept weights are again 2:4 sparse); with it
  * off the problem is the layer itself.  Where the layer's plan is the
- * wave-specialised input-patch kernel (and, with vSPARQ off, the layer is a
- * plain 8-bit one) the weights go to the sparse matrix instruction as its
- * sparse operand; otherwise the decompressed weights run on the dense path.
+ * wave-specialised input-patch kernel the weights go to the sparse matrix
+ * instruction as its sparse operand; otherwise the decompressed weights run
+ * on the dense path.
  * sparq_sparse24_plan reports which (a text line as from sparq_conv_plan plus
  * "expanded_x4" and "sparse_mfma" / "dense_mfma").
  * packed: 256-byte aligned, sparq_sparse24_packed_bytes() bytes, filled once
