@@ -108,3 +108,35 @@ def test_plan_rejects_bad_arguments(lib):
     ok = Desc(1, 8, 8, 64, 64, 3, 3, 1, 1, 1, 1)
     assert lib.sparq_conv_plan(ctypes.byref(ok), ctypes.byref(m), None, 0) == 1
     assert lib.sparq_conv_plan(ctypes.byref(ok), ctypes.byref(Mode(5, 1, 0, 0)), buf, len(buf)) == 1
+
+
+def sparse_plan(lib, d, m):
+    buf = ctypes.create_string_buffer(256)
+    assert lib.sparq_sparse24_plan(ctypes.byref(d), ctypes.byref(m), buf, len(buf)) == 0
+    return buf.value.decode()
+
+
+def test_sparse24_plan_names_the_matrix_instruction(lib):
+    """2:4 pruned weights: the sparse matrix instruction wherever the (expanded) layer takes the wave-specialised
+    input-patch kernel, for every mode; the dense kernels where it does not; and the packed buffer holds both forms."""
+    lib.sparq_sparse24_packed_bytes.restype = ctypes.c_size_t
+    conv = Desc(64, 32, 32, 512, 512, 3, 3, 1, 1, 1, 1)
+    for m in (Mode(4, 0x1F, 1, 1), Mode(4, 0x1F, 1, 0), Mode(4, 0x15, 0, 0), Mode(3, 0x3F, 1, 0), Mode(8, 1, 0, 0)):
+        text = sparse_plan(lib, conv, m)
+        assert text.startswith("conv_patch_kernel tile=128x256") and text.endswith("sparse_mfma"), text
+        assert ("expanded_x4" in text) == bool(m.pair and m.window_bits != 8), text
+    thin = Desc(2, 8, 8, 4, 8, 1, 1, 1, 1, 0, 0)                      # expands to 16 channels: taps are not step-aligned
+    assert sparse_plan(lib, thin, Mode(4, 0x1F, 1, 1)).endswith("dense_mfma")
+    assert lib.sparq_set_tuning(b"path=gather") == 0
+    try:
+        assert sparse_plan(lib, conv, Mode(4, 0x1F, 1, 1)).endswith("dense_mfma")
+    finally:
+        assert lib.sparq_set_tuning(None) == 0
+    m = Mode(4, 0x1F, 1, 1)
+    lib.sparq_packed_bytes.restype = ctypes.c_size_t
+    eff = Desc(64, 32, 32, 2048, 512, 3, 3, 1, 1, 1, 1)
+    dense_tiles = lib.sparq_packed_bytes(ctypes.byref(eff))
+    kp_np = 9 * 2048 * 512
+    assert lib.sparq_sparse24_packed_bytes(ctypes.byref(conv), ctypes.byref(m)) >= dense_tiles + kp_np + kp_np // 2 + kp_np // 8
+    buf = ctypes.create_string_buffer(64)
+    assert lib.sparq_sparse24_plan(ctypes.byref(Desc(1, 4, 4, 6, 8, 1, 1, 1, 1, 0, 0)), ctypes.byref(m), buf, len(buf)) == 1   # C % 4
