@@ -109,6 +109,31 @@ def test_sparse24_on_the_sparse_matrix_instruction(sq, oracle, layer):
     assert any(p.endswith("sparse_mfma") for p in seen), seen
 
 
+@pytest.mark.parametrize("layer", [SPARSE_MFMA_LAYERS[0], SPARSE_MFMA_LAYERS[5]], ids=lambda l: l.name)
+def test_sparse_instruction_kernel_with_one_output(sq, oracle, layer):
+    """int32 accumulators alone and fp32 results alone (each its own copy of the epilogue)."""
+    rng = S.rng_for(10, 200 + SPARSE_MFMA_LAYERS.index(layer))
+    x = S.gen_activations(layer.x_shape(), layer.zf, rng)
+    wv, wi = S.gen_sparse24_weights(layer.w_shape(), rng)
+    sc = S.gen_scales(layer.N, rng)
+    ref_acc, ref_out = oracle.conv_gemm_sparse24(x, wv, wi, layer.stride, layer.pad, scale=sc, **layer.mode.kwargs())
+    dev = torch.device("cuda:0")
+    d = sq.conv_desc(layer.B, layer.H, layer.W, layer.C, layer.N, layer.KH, layer.KW, layer.stride, layer.pad)
+    m = sq.mode(*layer.mode.astuple())
+    assert sq.sparq_sparse24_plan(d, m).endswith("sparse_mfma")
+    xd, vd, idd, sd = (torch.from_numpy(a).to(dev) for a in (x, wv, wi, sc))
+    packed = torch.empty(sq.sparq_sparse24_packed_bytes(d, m), dtype=torch.uint8, device=dev)
+    sq.sparq_pack_weights_sparse24(vd, idd, d, m, packed)
+    ws = torch.empty(max(sq.sparq_sparse24_workspace_bytes(d, m), 1), dtype=torch.uint8, device=dev)
+    acc = torch.full((layer.M, layer.N), -7, dtype=torch.int32, device=dev)
+    out = torch.full((layer.M, layer.N), -7.0, dtype=torch.float32, device=dev)
+    sq.sparq_conv_gemm_sparse24(xd, packed, d, m, acc=acc, workspace=ws)
+    sq.sparq_conv_gemm_sparse24(xd, packed, d, m, scale=sd, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc.cpu().numpy(), ref_acc)
+    assert np.all(np.abs(out.cpu().numpy().astype(np.float64) - ref_out) <= 1e-6 * np.abs(ref_out))
+
+
 def test_extreme_values(sq, oracle):
     """All activations 255 or 0 in a pattern that makes every partner case occur, weights at -127 / 127."""
     layer = S.ConvLayer("sp_extreme", 1, 6, 6, 64, 32, 3, 3, (1, 1), (1, 1), 0.5, M45)
