@@ -581,9 +581,8 @@ __global__ __launch_bounds__(Cfg::kThreads, Cfg::kWgPerCu * Cfg::kThreads / 256)
                     const uint8_t* xrd = xr + (le >> 4) * kSparseRowPitch + (le & 15) * 16;
                     const int nrun = n0 + wn * Cfg::kWTN + (le & 15) * 4;            // first channel of this lane's 16 bytes
                     const uint32_t run_off = (uint32_t)((wm * Cfg::kWTM + (le >> 4)) * pitch + nrun * 4);
-                    // the lane's four channels' constants: requested here, ahead of every store (a request between
-                    // stores would wait for their round trips) and not at the tile's start (the step loop has no
-                    // registers to spare for them)
+                    // the lane's four channels' constants: requested here, ahead of every store, and not at the
+                    // tile's start (the step loop has no registers to spare for them)
                     static_assert(!SP || Cfg::kWTN == 64, "64 channels per wavefront");
                     int32_t corr4[4];
                     float sc4[4];
