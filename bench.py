@@ -530,7 +530,22 @@ def main():
             e["note"] = ("value counts the dense layer's operations; with pairing on the expanded problem holds 4x the channels, "
                          "on the sparse matrix instruction (plan ends in sparse_mfma) that is 2x the dense layer's matrix instructions")
             also.append(e)
-            del wvd, wid, sp, ws
+            del sp, ws
+            # the same pruned weights with vSPARQ off: no expansion, the layer itself on the sparse matrix instruction
+            if L.mode.window_bits < 8 and L.mode.pair:
+                m1 = sq.mode(L.mode.window_bits, L.mode.shift_mask, L.mode.round_nearest, 0)
+                sp = torch.empty(sq.sparq_sparse24_packed_bytes(dom["d"], m1), dtype=torch.uint8, device=dev)
+                sq.sparq_pack_weights_sparse24(wvd, wid, dom["d"], m1, sp)
+                ws = torch.empty(max(sq.sparq_sparse24_workspace_bytes(dom["d"], m1), 1), dtype=torch.uint8, device=dev)
+                ms7 = time_calls(torch, lambda i: sq.sparq_conv_gemm_sparse24(dom["x"], sp, dom["d"], m1, scale=dom["sc"], out=dom["out"],
+                                                                              workspace=ws), args.warmup, args.steps)
+                e = entry(wl_name + ", 2:4 pruned weights with vSPARQ off (each picked activation trimmed alone: the layer itself, "
+                                    "half its weights)", [L], ms7, 4)
+                e["plan"] = sq.sparq_sparse24_plan(dom["d"], m1)
+                e["note"] = "value counts the dense layer's operations; the dense layer (all weights kept) is this run's headline figure"
+                also.append(e)
+                del sp, ws
+            del wvd, wid
         torch.cuda.empty_cache()
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload ----
